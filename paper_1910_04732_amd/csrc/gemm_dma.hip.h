@@ -35,7 +35,9 @@ namespace flop {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+#ifndef FLOP_LDS_PTR   // a host build of the address arithmetic defines its own
 #define FLOP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#endif
 
 // s_waitcnt that waits only for vmcnt <= N (lgkmcnt / expcnt left alone).
 template <int N>
