@@ -59,7 +59,8 @@ typedef enum {
     FLOP_ERR_WORKSPACE = -6, /* workspace missing or smaller than flop_workspace_bytes() */
     FLOP_ERR_ALIGN = -7,     /* workspace not 256-byte aligned */
     FLOP_ERR_HIP = -8,       /* a HIP launch reported an error */
-    FLOP_ERR_ALIAS = -9      /* an output overlaps an input that the same launch still reads */
+    FLOP_ERR_ALIAS = -9,     /* an output overlaps an input that the same launch still reads */
+    FLOP_ERR_SCRATCH = -10   /* the problem needs more scratch than the library's static device array holds */
 } flop_status;
 
 typedef enum { FLOP_F32 = 0, FLOP_BF16 = 1 } flop_dtype;
@@ -127,6 +128,26 @@ int flop_bwd(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
              void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
              float* dlog_alpha, int accumulate,
              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * flop_bwd for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same arguments without the workspace.  The
+ * scratch that flop_bwd takes from its workspace (dh, the column-sum partials, k-split partials) lives in one
+ * static device array of FLOP_STATIC_SCRATCH_BYTES inside the library, resolved once per device on the first
+ * call there; this call allocates and frees nothing.  A problem whose
+ * flop_workspace_bytes(FLOP_OP_BWD, dt, n, d, r, dout) exceeds FLOP_STATIC_SCRATCH_BYTES is refused with
+ * FLOP_ERR_SCRATCH before anything is enqueued.  Results equal flop_bwd's bit for bit.  Nothing in the
+ * array has to start at zero (every byte the kernels read has been written by the same call).  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or graphs
+ * replayed concurrently) race and must be serialised by the caller.
+ */
+#define FLOP_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int flop_bwd_static(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                    const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                    const void* Q, int64_t ldq, const void* P, int64_t ldp,
+                    const float* z, const float* dzda, const void* g_saved, int64_t ldg,
+                    void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
+                    float* dlog_alpha, int accumulate, void* stream);
 
 /*
  * flop_bwd with the last stage of the gate gradient left for later (the optimiser needs dlog_alpha

@@ -816,6 +816,32 @@ int bwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
     return FLOP_OK;
 }
 
+// ------------------------------------------------------------------------
+// Scratch of flop_bwd_static: one array in device memory per GPU, part of the code object.  In host code the
+// array's name only stands for the symbol; its device address is looked up once per device and kept.
+// ------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[FLOP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct ScratchTable {
+    std::mutex mu;
+    void* ptr[kMaxDevices] = {};
+} g_scratch;
+
+// Device address of `scratch` on the current device, or nullptr if the lookup fails.
+void* scratch_ptr()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch.mu);
+    if (!g_scratch.ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch.ptr[dev] = p;
+    }
+    return g_scratch.ptr[dev];
+}
+
 inline int l0_blocks(int64_t n)
 {
     int64_t b = (n + (int64_t)kStreamThreads * 16 - 1) / ((int64_t)kStreamThreads * 16);
@@ -841,6 +867,7 @@ const char* flop_status_string(int status)
         case FLOP_ERR_ALIGN: return "workspace not 256-byte aligned";
         case FLOP_ERR_HIP: return "HIP launch failed";
         case FLOP_ERR_ALIAS: return "an output overlaps an input of the same launch";
+        case FLOP_ERR_SCRATCH: return "problem needs more scratch than the static device array holds (FLOP_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }
@@ -1008,6 +1035,23 @@ int flop_bwd(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
 {
     return bwd_impl(dt, n, d, r, dout, dy, lddy, x, ldx, Q, ldq, P, ldp, z, dzda, nullptr, g_saved, ldg, dx, lddx,
                     dQ, lddq, dP, lddp, dlog_alpha, accumulate, workspace, workspace_bytes, stream);
+}
+
+int flop_bwd_static(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                    const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                    const void* Q, int64_t ldq, const void* P, int64_t ldp,
+                    const float* z, const float* dzda, const void* g_saved, int64_t ldg,
+                    void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
+                    float* dlog_alpha, int accumulate, void* stream)
+{
+    if (!valid_dtype(dt)) return FLOP_ERR_DTYPE;
+    if (n < 0 || d <= 0 || r <= 0 || dout <= 0 || n > kMaxDim || d > kMaxDim || r > kMaxDim || dout > kMaxDim)
+        return FLOP_ERR_SHAPE;
+    if (flop_workspace_bytes(FLOP_OP_BWD, dt, n, d, r, dout) > FLOP_STATIC_SCRATCH_BYTES) return FLOP_ERR_SCRATCH;
+    void* ws = scratch_ptr();
+    if (!ws) return FLOP_ERR_HIP;
+    return bwd_impl(dt, n, d, r, dout, dy, lddy, x, ldx, Q, ldq, P, ldp, z, dzda, nullptr, g_saved, ldg, dx, lddx,
+                    dQ, lddq, dP, lddp, dlog_alpha, accumulate, ws, FLOP_STATIC_SCRATCH_BYTES, stream);
 }
 
 int flop_bwd_deferred(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,

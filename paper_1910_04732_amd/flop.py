@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libflop_hip.so")
 
 FLOP_F32, FLOP_BF16 = 0, 1
 FLOP_GATE_TRAIN, FLOP_GATE_DETERMINISTIC = 0, 1
+FLOP_STATIC_SCRATCH_BYTES = 16 << 20
 FLOP_OP_FWD, FLOP_OP_BWD, FLOP_OP_EXPECTED_L0, FLOP_OP_COMPACT, FLOP_OP_EMBED_FWD, FLOP_OP_EMBED_BWD, FLOP_OP_GATE_GRAD = range(7)
 
 
@@ -80,6 +81,8 @@ def lib():
         L.flop_fwd.argtypes = [_int] + [_i64] * 4 + [_vp, _i64] * 3 + [_vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
         L.flop_bwd.argtypes = ([_int] + [_i64] * 4 + [_vp, _i64] * 4 + [_vp, _vp, _vp, _i64]
                                + [_vp, _i64] * 3 + [_vp, _int, _vp, _sz, _vp])
+        L.flop_bwd_static.argtypes = L.flop_bwd.argtypes[:-3] + [_vp]
+        L.flop_bwd_static.restype = _int
         L.flop_bwd_deferred.argtypes = L.flop_bwd.argtypes + [ctypes.POINTER(flop_gate_grad_pending)]
         L.flop_bwd_boundary.argtypes = L.flop_bwd.argtypes[:-1] + [ctypes.POINTER(flop_boundary_job), _vp]
         L.flop_fwd_sampling.argtypes = ([_int] + [_i64] * 4 + [_vp, _i64] * 3 + [ctypes.POINTER(flop_boundary_job), _i64]
@@ -217,6 +220,27 @@ def flop_bwd(dy, x, Q, P, z, dzda, g_saved, dx, dQ, dP, dlog_alpha, ws, accumula
                           _vec(z, "z"), _vec(dzda, "dzda"), gp, ldg, dxp, lddx, dqp, lddq, dpp, lddp,
                           _vec(dlog_alpha, "dlog_alpha"), 1 if accumulate else 0,
                           _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)), "flop_bwd")
+    return dx, dQ, dP, dlog_alpha
+
+
+def flop_bwd_static(dy, x, Q, P, z, dzda, g_saved, dx, dQ, dP, dlog_alpha, accumulate=False, stream=None):
+    """flop_bwd with its scratch in the library's static device array: no workspace argument, no allocation."""
+    dt = _dt(x)
+    n, d = x.shape
+    r, dout = Q.shape[0], P.shape[0]
+    assert dy.shape == (n, dout) and Q.shape == (r, d) and P.shape == (dout, r) and g_saved.shape == (n, r)
+    dyp, lddy = _mat(dy, "dy")
+    xp, ldx = _mat(x, "x")
+    qp, ldq = _mat(Q, "Q")
+    pp, ldp = _mat(P, "P")
+    gp, ldg = _mat(g_saved, "g_saved")
+    dxp, lddx = (None, 0) if dx is None else _mat(dx, "dx")
+    dqp, lddq = (None, 0) if dQ is None else _mat(dQ, "dQ")
+    dpp, lddp = (None, 0) if dP is None else _mat(dP, "dP")
+    _check(lib().flop_bwd_static(dt, n, d, r, dout, dyp, lddy, xp, ldx, qp, ldq, pp, ldp,
+                                 _vec(z, "z"), _vec(dzda, "dzda"), gp, ldg, dxp, lddx, dqp, lddq, dpp, lddp,
+                                 _vec(dlog_alpha, "dlog_alpha"), 1 if accumulate else 0, _stream(stream)),
+           "flop_bwd_static")
     return dx, dQ, dP, dlog_alpha
 
 

@@ -91,6 +91,10 @@ void plain_pass(flop_dtype dt, std::vector<Layer>& layers, int64_t G, const floa
         must(flop_bwd(dt, t.n, t.d, t.r, t.dout, t.dy.p, t.dout, t.x.p, t.d, t.Q.p, t.d, t.P.p, t.r, z.f() + t.off,
                       dz.f() + t.off, t.g.p, t.r, t.dx.p, t.d, t.dQ.p, t.d, t.dP.p, t.r, t.da.f(), 0, t.ws.p, t.ws.bytes, nullptr),
              "flop_bwd");
+        if (flop_workspace_bytes(FLOP_OP_BWD, dt, t.n, t.d, t.r, t.dout) <= FLOP_STATIC_SCRATCH_BYTES)
+            must(flop_bwd_static(dt, t.n, t.d, t.r, t.dout, t.dy.p, t.dout, t.x.p, t.d, t.Q.p, t.d, t.P.p, t.r, z.f() + t.off,
+                                 dz.f() + t.off, t.g.p, t.r, t.dx.p, t.d, t.dQ.p, t.d, t.dP.p, t.r, t.da.f(), 0, nullptr),
+                 "flop_bwd_static");
     }
 }
 
