@@ -14,7 +14,9 @@
  *  - All matrices are row-major.  Leading dimensions (ld*) are in ELEMENTS and
  *    must be >= the logical number of columns.
  *  - Every data pointer is a DEVICE pointer owned by the caller; the library
- *    allocates nothing, frees nothing and keeps no state between calls.
+ *    allocates nothing, frees nothing and keeps no state between calls
+ *    (flop_bwd_static's scratch array excepted, see there; the measurement aids of
+ *    flop_bench.h, a separate header, keep state of their own).
  *    Scalars that are marked "host" are plain values.
  *  - x, Q, P, g, y and their gradients have the element type `dt` (float32 or
  *    bfloat16).  log_alpha, u, z, dzda, dlog_alpha and every reduction are
@@ -457,31 +459,6 @@ int flop_lagrangian(const float* size_sum, const float* size_grad, int64_t n_gat
  * (0 when it needs none).  For FLOP_OP_EXPECTED_L0 pass the gate count as n; for the
  * embedding ops pass the token count as n and the sum of the cluster dimensions as r. */
 size_t flop_workspace_bytes(int op, flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout);
-
-/*
- * Per-launch timing of the contraction kernel, for benchmarks (not part of the
- * method).  Between flop_trace_begin and flop_trace_end every contraction launch
- * made by flop_fwd / flop_bwd stamps a hipEvent pair at the kernel's begin and
- * end (hipExtLaunchKernelGGL); at most `capacity` launches are recorded.  flop_trace_end waits for the
- * recorded work, fills up to max_records records (host memory) in launch order
- * and writes how many to *count.  kernel_id = 1000 * flop_dtype + mean tile edge,
- * plus 100 for the asynchronous-staging bfloat16 kernel (e.g. 1228: that kernel with
- * 128x128 tiles, 1196: 128x64, 64: float32 generic kernel with 64x64 tiles); flops = 2 M N K summed over the products
- * of the launch; ms = elapsed time between the two events.  The events are host
- * objects the library keeps for reuse; do not trace while capturing a HIP graph.
- */
-typedef struct { int kernel_id; int tiles; double flops; float ms; } flop_trace_record;
-int flop_trace_begin(int capacity);
-int flop_trace_end(flop_trace_record* out, int max_records, int* count);
-
-/*
- * Matrix-core rate probe, for benchmarks (not part of the method): `blocks` workgroups of four
- * wavefronts each issue `iters` rounds of four independent 32x32 matrix instructions of the given type
- * (bfloat16: 32x32x16, float32: 32x32x2) on register operands and nothing else.  The caller times the
- * launch; *flops (host, nullable) receives the flop count of the launch.  sink: device, at least 64
- * floats, overwritten.  FLOP_ERR_SHAPE for iters outside 1..2^24 or blocks outside 1..65536.
- */
-int flop_mfma_probe(flop_dtype dt, int64_t iters, int32_t blocks, float* sink, double* flops, void* stream);
 
 /* Static description of a flop_status. */
 const char* flop_status_string(int status);

@@ -17,6 +17,7 @@
 #include "gemm_lowrank.hip.h"
 #include "stream_kernels.hip.h"
 #include "embed_kernels.hip.h"
+#include "bench_hooks.h"
 
 using namespace flop;
 
@@ -52,27 +53,6 @@ struct GemmDesc {
     const float* gate_alpha; const float* gate_u; float gate_beta, gate_l, gate_r;
 };
 
-// ------------------------------------------------------------------------
-// Optional per-launch timing of the contraction kernel (flop_trace_*):
-// a hipEvent pair brackets each launch on the caller's stream.
-// ------------------------------------------------------------------------
-struct TraceSlot { hipEvent_t start, stop; int kernel_id; int tiles; double flops; };
-struct TraceState {
-    std::mutex mu;
-    bool on = false;
-    std::vector<TraceSlot> slots;   // events are created once and reused
-    size_t used = 0, capacity = 0;
-} g_trace;
-
-inline TraceSlot* trace_acquire(int kernel_id, int tiles, double flops)
-{
-    std::lock_guard<std::mutex> lk(g_trace.mu);
-    if (!g_trace.on || g_trace.used >= g_trace.capacity) return nullptr;
-    TraceSlot* s = &g_trace.slots[g_trace.used++];
-    s->kernel_id = kernel_id; s->tiles = tiles; s->flops = flops;
-    return s;
-}
-
 // Kernels that need more dynamic LDS than the default limit get the attribute once per device (a function's
 // attributes belong to the device it is loaded on); which devices are done is a bit mask.
 struct AttrOnce {
@@ -89,7 +69,7 @@ struct AttrOnce {
 // One launch of a tile kernel over up to kMaxGroup products.  Products are ordered
 // by decreasing k extent so that the longest tiles are dispatched first.
 template <int ES, int BM, int BN>
-int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, int kernel_id,
+int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, int kernel_id, int threads,
                  const GemmDesc* d_in, int count, hipStream_t stream, const BoundaryRider* rider = nullptr,
                  bool* carried = nullptr)
 {
@@ -142,11 +122,11 @@ int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, in
         if (carried) *carried = true;
     }
     const dim3 grid((unsigned)(grp.tile_blocks + grp.rider_blocks));
-    TraceSlot* ts = g_trace.on ? trace_acquire(kernel_id, tiles, flops) : nullptr;
+    TraceSlot* ts = trace_acquire(kernel_id, tiles, flops);
     if (ts)   // the dispatch itself stamps the two events at kernel begin and end
-        hipExtLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), lds, stream, ts->start, ts->stop, 0, grp);
+        hipExtLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, ts->start, ts->stop, 0, grp);
     else
-        hipLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), lds, stream, grp);
+        hipLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, grp);
     return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
 }
 
@@ -155,15 +135,39 @@ int launch_generic(const GemmDesc* d, int count, hipStream_t stream)
 {
     static AttrOnce attr;
     return launch_tiles<sizeof(T), B, B>(gemm_tile_kernel<T, B, B>, gemm_lds_bytes<B, B>(), &attr,
-                                         (sizeof(T) == 2 ? 1000 : 0) + B, d, count, stream);
+                                         (sizeof(T) == 2 ? 1000 : 0) + B, kGemmThreads, d, count, stream);
 }
 
-template <int BM, int BN, int NSTAGE, bool BKM, int XFER>
+// Block shapes of the bf16 transfer kernel (see TileShape): tile, stage buffers, wave grid, k groups.
+using Shape128x128 = TileShape<128, 128, 2, 2, 2, 1>;     // 64 KB, two blocks per compute unit
+using Shape128x64 = TileShape<128, 64, 3, 2, 2, 1>;       // 72 KB
+using Shape64x64 = TileShape<64, 64, 3, 2, 2, 1>;         // 48 KB, three blocks per compute unit
+using Shape64x64g2 = TileShape<64, 64, 3, 2, 2, 2>;       // 96 KB, 512 threads: few tiles, long contraction
+using Shape64x96g2 = TileShape<64, 96, 3, 2, 3, 2>;       // 144 KB, 768 threads: 256 equal tiles on 2048 x 768
+using Shape128x64g2 = TileShape<128, 64, 3, 2, 2, 2>;     // 144 KB, 512 threads
+using Shape128x128g2 = TileShape<128, 128, 2, 2, 2, 2>;   // 128 KB, 512 threads
+using Shape256x128 = TileShape<256, 128, 3, 4, 2, 1>;     // 144 KB, 512 threads: 85 flop per staged byte
+using Shape64x64g4 = TileShape<64, 64, 2, 2, 2, 4>;       // 128 KB, 1024 threads
+using Shape64x96 = TileShape<64, 96, 3, 2, 3, 1>;         // 72 KB, 384 threads
+using Shape64x64g2n2 = TileShape<64, 64, 2, 2, 2, 2>;     // 64 KB, 512 threads, two blocks per compute unit
+using Shape64x96g2n2 = TileShape<64, 96, 2, 2, 3, 2>;     // 96 KB, 768 threads
+using Shape128x64g2n2 = TileShape<128, 64, 2, 2, 2, 2>;   // 96 KB, 512 threads
+using Shape64x64n2 = TileShape<64, 64, 2, 2, 2, 1>;       // 32 KB, five blocks per compute unit
+constexpr int kNumShapes = kNumTileShapes;
+struct ShapeInfo { int bm, bn, groups, blocks_per_cu; double step_us; };   // step_us: one 64-k step of a group
+constexpr ShapeInfo kShapes[kNumShapes] = {
+    {128, 128, 1, 2, 0.82}, {128, 64, 1, 2, 0.59}, {64, 64, 1, 3, 0.43}, {64, 64, 2, 1, 0.45}, {64, 96, 2, 1, 0.50},
+    {128, 64, 2, 1, 0.62}, {128, 128, 2, 1, 0.85}, {256, 128, 1, 1, 1.10}, {64, 64, 4, 1, 0.50}, {64, 96, 1, 2, 0.50},
+    {64, 64, 2, 2, 0.45}, {64, 96, 2, 1, 0.50}, {128, 64, 2, 1, 0.62}, {64, 64, 1, 5, 0.43},
+};
+
+template <typename SH, bool BKM, int XFER>
 int launch_dma(const GemmDesc* d, int count, hipStream_t stream, const BoundaryRider* rider, bool* carried)
 {
     static AttrOnce attr;
-    return launch_tiles<2, BM, BN>(gemm_bf16_dma_kernel<BM, BN, NSTAGE, BKM, XFER>, gemm_dma_lds_bytes<BM, BN, NSTAGE>(),
-                                   &attr, 1100 + (BM + BN) / 2, d, count, stream, rider, carried);
+    return launch_tiles<2, SH::BM, SH::BN>(gemm_bf16_dma_kernel<SH, BKM, XFER>, gemm_dma_lds_bytes<SH>(), &attr,
+                                           1100 + (SH::BM + SH::BN) / 2 + 10000 * (SH::G - 1), SH::THREADS, d, count,
+                                           stream, rider, carried);
 }
 
 // The DMA kernel describes each operand with a buffer descriptor whose range is below 2 GiB.  For a
@@ -242,15 +246,7 @@ inline int plan_ksplit(int64_t M, int64_t N, int64_t K)
 // are the critical path of the launch.
 inline int pick_cfg(const GemmDesc* d, int count, bool transfer_kernel)
 {
-#ifdef FLOP_TUNING_HOOKS   // build-time option for tile-shape experiments: comma list, one entry per launch
-    static const char* env = getenv("FLOP_TILE_CFG");
-    if (env && *env) {
-        static int pos = 0;
-        int n = 0; int vals[64];
-        for (const char* c = env; *c && n < 64; ++c) if (*c >= '0' && *c <= '9') vals[n++] = *c - '0';
-        if (n) return vals[pos++ % n];
-    }
-#endif
+    if (transfer_kernel && forced_tile_shape() >= 0) return forced_tile_shape();   // flop_bench.h
     bool narrow = true;   // no product wider than 64 columns: 128-wide tiles would be half empty
     for (int i = 0; i < count; ++i) narrow = narrow && d[i].N <= 64;
     if (!transfer_kernel) {   // generic kernel: 128x128 when that still gives every compute unit work, else 64x64
@@ -326,19 +322,33 @@ inline size_t ksplit_bytes(int64_t M, int64_t N, int64_t K, int64_t lda_rows = 0
 template <bool BKM, int XFER>
 int launch_dma_cfg(int cfg, const GemmDesc* d, int count, hipStream_t stream, const BoundaryRider* rider, bool* carried)
 {
-    switch (cfg) {
-        case 0: return launch_dma<128, 128, 2, BKM, XFER>(d, count, stream, rider, carried);
-        case 1: return launch_dma<128, 64, 3, BKM, XFER>(d, count, stream, rider, carried);
-#ifdef FLOP_TUNING_HOOKS
-        case 3: return launch_dma<128, 64, 5, BKM, 16>(d, count, stream, rider, carried);
-        case 4: return launch_dma<64, 64, 5, BKM, 16>(d, count, stream, rider, carried);
-        case 5: return launch_dma<128, 128, 3, BKM, 16>(d, count, stream, rider, carried);
-        case 6: return launch_dma<128, 128, 4, BKM, 16>(d, count, stream, rider, carried);
-        case 7: return launch_dma<64, 64, 4, BKM, 16>(d, count, stream, rider, carried);
-        case 8: return launch_dma<128, 64, 4, BKM, 16>(d, count, stream, rider, carried);
-#endif
-        default: return launch_dma<64, 64, 3, BKM, XFER>(d, count, stream, rider, carried);
+    if constexpr (XFER == 16) {
+        switch (cfg) {
+            case 3: return launch_dma<Shape64x64g2, BKM, 16>(d, count, stream, rider, carried);
+            case 4: return launch_dma<Shape64x96g2, BKM, 16>(d, count, stream, rider, carried);
+            case 5: return launch_dma<Shape128x64g2, BKM, 16>(d, count, stream, rider, carried);
+            case 6: return launch_dma<Shape128x128g2, BKM, 16>(d, count, stream, rider, carried);
+            case 7: return launch_dma<Shape256x128, BKM, 16>(d, count, stream, rider, carried);
+            case 8: return launch_dma<Shape64x64g4, BKM, 16>(d, count, stream, rider, carried);
+            case 9: return launch_dma<Shape64x96, BKM, 16>(d, count, stream, rider, carried);
+            case 10: return launch_dma<Shape64x64g2n2, BKM, 16>(d, count, stream, rider, carried);
+            case 11: return launch_dma<Shape64x96g2n2, BKM, 16>(d, count, stream, rider, carried);
+            case 12: return launch_dma<Shape128x64g2n2, BKM, 16>(d, count, stream, rider, carried);
+            case 13: return launch_dma<Shape64x64n2, BKM, 16>(d, count, stream, rider, carried);
+            default: break;
+        }
     }
+    switch (cfg) {   // rows that are only 4-byte aligned take the three shapes of four wavefronts
+        case 0: case 6: case 7: return launch_dma<Shape128x128, BKM, XFER>(d, count, stream, rider, carried);
+        case 1: case 5: case 12: return launch_dma<Shape128x64, BKM, XFER>(d, count, stream, rider, carried);
+        default: return launch_dma<Shape64x64, BKM, XFER>(d, count, stream, rider, carried);
+    }
+}
+// Tile rows of the shape that launch_dma_cfg<., XFER> runs for cfg
+inline int cfg_tile_rows(int cfg, int xfer)
+{
+    if (xfer == 16) return kShapes[cfg].bm;
+    return (cfg == 0 || cfg == 6 || cfg == 7 || cfg == 1 || cfg == 5 || cfg == 12) ? 128 : 64;
 }
 
 // Whether the store-bound kernel for ranks up to 256 takes the product: k-contiguous operands and 16-byte rows
@@ -377,7 +387,7 @@ int launch_lowrank(const GemmDesc& g, hipStream_t stream)
     }
     const int64_t blocks = (int64_t)pr.splits * pr.bands;
     if (blocks > (1 << 30)) return FLOP_ERR_SHAPE;
-    TraceSlot* ts = g_trace.on ? trace_acquire(1300, pr.bands * pr.tiles_n, 2.0 * (double)g.M * (double)g.N * (double)g.K) : nullptr;
+    TraceSlot* ts = trace_acquire(1300, pr.bands * pr.tiles_n, 2.0 * (double)g.M * (double)g.N * (double)g.K);
     void (*kernel)(const LowRankProblem) =
         variant == 0 ? gemm_bf16_lowrank_kernel<4, 64> : variant == 1 ? gemm_bf16_lowrank_kernel<8, 64> :
         variant == 2 ? gemm_bf16_lowrank_kernel<12, 32> : gemm_bf16_lowrank_kernel<16, 32>;
@@ -438,7 +448,7 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
             }
         }
         if (xfer) {
-            if (fused_tile_rows && !dot_lost) *fused_tile_rows = (cfg == 0 || cfg == 1 || cfg == 3 || cfg == 5) ? 128 : 64;
+            if (fused_tile_rows && !dot_lost) *fused_tile_rows = cfg_tile_rows(cfg, xfer);
             int rc;
             if (xfer == 16) rc = ds[0].b_kmajor ? launch_dma_cfg<true, 16>(cfg, ds, count, stream, rider, carried) : launch_dma_cfg<false, 16>(cfg, ds, count, stream, rider, carried);
             else rc = ds[0].b_kmajor ? launch_dma_cfg<true, 4>(cfg, ds, count, stream, rider, carried) : launch_dma_cfg<false, 4>(cfg, ds, count, stream, rider, carried);
@@ -870,56 +880,6 @@ const char* flop_status_string(int status)
         case FLOP_ERR_SCRATCH: return "problem needs more scratch than the static device array holds (FLOP_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
-}
-
-int flop_mfma_probe(flop_dtype dt, int64_t iters, int32_t blocks, float* sink, double* flops, void* stream)
-{
-    if (dt != FLOP_F32 && dt != FLOP_BF16) return FLOP_ERR_DTYPE;
-    if (iters <= 0 || iters > (1 << 24) || blocks <= 0 || blocks > (1 << 16)) return FLOP_ERR_SHAPE;
-    if (!sink) return FLOP_ERR_NULL;
-    const double per_mfma = dt == FLOP_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
-    if (flops) *flops = per_mfma * kProbeChains * (double)iters * kProbeWavesPerBlock * blocks;
-    if (dt == FLOP_BF16)
-        hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3((unsigned)blocks), dim3(64 * kProbeWavesPerBlock), 0, (hipStream_t)stream,
-                           (int)iters, sink);
-    else
-        hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3((unsigned)blocks), dim3(64 * kProbeWavesPerBlock), 0, (hipStream_t)stream,
-                           (int)iters, sink);
-    return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
-}
-
-int flop_trace_begin(int capacity)
-{
-    if (capacity <= 0 || capacity > (1 << 20)) return FLOP_ERR_SHAPE;
-    std::lock_guard<std::mutex> lk(g_trace.mu);
-    while (g_trace.slots.size() < (size_t)capacity) {
-        TraceSlot s{};
-        if (hipEventCreate(&s.start) != hipSuccess || hipEventCreate(&s.stop) != hipSuccess) return FLOP_ERR_HIP;
-        g_trace.slots.push_back(s);
-    }
-    g_trace.capacity = (size_t)capacity;
-    g_trace.used = 0;
-    g_trace.on = true;
-    return FLOP_OK;
-}
-
-int flop_trace_end(flop_trace_record* out, int max_records, int* count)
-{
-    if (!count || (max_records > 0 && !out)) return FLOP_ERR_NULL;
-    std::lock_guard<std::mutex> lk(g_trace.mu);
-    g_trace.on = false;
-    int n = 0;
-    for (size_t i = 0; i < g_trace.used && n < max_records; ++i) {
-        TraceSlot& s = g_trace.slots[i];
-        if (hipEventSynchronize(s.stop) != hipSuccess) return FLOP_ERR_HIP;
-        float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, s.start, s.stop) != hipSuccess) return FLOP_ERR_HIP;
-        out[n].kernel_id = s.kernel_id; out[n].tiles = s.tiles; out[n].flops = s.flops; out[n].ms = ms;
-        ++n;
-    }
-    *count = n;
-    g_trace.used = 0;
-    return FLOP_OK;
 }
 
 size_t flop_workspace_bytes(int op, flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout)

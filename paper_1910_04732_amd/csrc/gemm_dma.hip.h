@@ -19,7 +19,15 @@
 //     is fetched with ds_read_b64_tr_b16, which transposes 4x16 blocks on the
 //     way into the MFMA operand layout;
 //   * blocks map to tiles through locate_tile(): each XCD works on a contiguous
-//     range of every product's tiles and re-uses panels in its own L2.
+//     range of every product's tiles and re-uses panels in its own L2;
+//   * a block is G groups of WM x WN wavefronts.  Every group covers the whole
+//     BM x BN tile (a wavefront owns a (BM/WM) x (BN/WN) part of it) but only
+//     every G-th 64-k step of the contraction, with stage buffers, transfers
+//     and accumulators of its own; the groups' sums are added through LDS before
+//     the epilogue.  A launch with few tiles per compute unit then has G times
+//     the bytes in flight per tile and G wavefronts per SIMD, and a tile takes
+//     1/G of the steps (the groups share the block's barriers: all take the
+//     same number of steps, a step beyond K is zero-filled).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -49,46 +57,65 @@ __device__ __forceinline__ void wait_vmcnt()
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // beyond any descriptor we build (ranges < 2 GiB)
 
-// Per-thread transfer plan of one operand tile: ROWS rows (m or n) by 64 k.
-template <int ROWS>
+// Swizzle of a [k][row] stage with S 64-byte segments per k row: segment index seg of k row krow is stored at
+// segment kr_swizzle<S>(krow, seg).  Four consecutive k rows (what one transposing fragment read touches per
+// 16 lanes) must land in four different 64-byte bank groups: with a row pitch of 128, 256 or 512 bytes the
+// segment is XOR-ed with bits of the k row; with 64 or 192 bytes consecutive rows already do.
+template <int S>
+__device__ __forceinline__ int kr_swizzle(int krow, int seg)
+{
+    static_assert(S == 1 || S == 2 || S == 3 || S == 4 || S == 8, "stage rows per operand: 32, 64, 96, 128 or 256");
+    if constexpr (S == 2) return seg ^ ((krow >> 1) & 1);
+    else if constexpr (S == 4 || S == 8) return seg ^ (krow & 3);
+    else return seg;
+}
+
+// Per-thread transfer plan of one operand stage: ROWS rows (m or n) by 64 k, filled by the NW wavefronts of a
+// group (ROWS a multiple of 8 NW: a wave instruction fills 64 slots of 16 bytes).  The group contracts the
+// k ranges [64 (s G + g), +64), s = 0 .. nk - 1.
+template <int ROWS, int NW>
 struct DmaPlan {
-    static constexpr int NV = ROWS / 32;          // 16-byte transfers per thread and step
-    uint32_t voff[NV];       // byte offset of each transfer at k0 = 0 (kOutOfRange: zero-fill)
-    uint32_t tail_bit[NV];   // kOutOfRange where the transfer lies beyond K in a partial last step
-    uint32_t step_bytes;     // added per 64-k step (scalar offset)
+    static_assert(ROWS % (8 * NW) == 0, "stage rows must divide among the group's wavefronts");
+    static constexpr int NV = ROWS / (8 * NW);    // 16-byte transfers per thread and step
+    uint32_t voff[NV];       // byte offset of each transfer at step 0 (kOutOfRange: zero-fill)
+    uint32_t tail_bit[NV];   // kOutOfRange where the transfer lies beyond K in the group's last step
+    uint32_t step_bytes;     // added per step (scalar offset)
 
     // kmajor: X[row*ld + k]      otherwise: X[k*ld + row]
-    __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid)
+    // tid: thread index inside the group; k_first: first k of the group (64 g); k_stride: 64 G; nk: steps
+    __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid, int k_first,
+                                         int k_stride, int nk)
     {
         const int wave = tid >> 6, lane = tid & 63;
-        const int ktail0 = (K / 64) * 64;   // first k of a partial last step
+        const int ktail0 = (nk - 1) * k_stride + k_first;   // first k of the group's last step
 #pragma unroll
         for (int p = 0; p < NV; ++p) {
-            const int pos = (p * 4 + wave) * 64 + lane;   // 16-byte slot inside the stage buffer
+            const int pos = (p * NW + wave) * 64 + lane;   // 16-byte slot inside the stage buffer
             if (kmajor) {
                 const int row = pos >> 3, cp = pos & 7;
                 const int c = cp ^ ((row >> 1) & 7);
-                voff[p] = (row0 + row < rows) ? (uint32_t)(((int64_t)(row0 + row) * ld + c * 8) * 2) : kOutOfRange;
+                voff[p] = (row0 + row < rows) ? (uint32_t)(((int64_t)(row0 + row) * ld + k_first + c * 8) * 2) : kOutOfRange;
                 tail_bit[p] = (ktail0 + c * 8 < K) ? 0u : kOutOfRange;
             } else {
                 constexpr int CPR = ROWS / 8;             // 16-byte chunks per k-row
                 constexpr int S = ROWS / 32;              // 64-byte segments per k-row
                 const int krow = pos / CPR, cc = pos % CPR;
-                const int f = (S == 2) ? ((krow >> 1) & 1) : (krow & 3);
-                const int seg = (cc >> 2) ^ f;
-                const int m = row0 + seg * 32 + (cc & 3) * 8;
-                voff[p] = (m < rows) ? (uint32_t)(((int64_t)krow * ld + m) * 2) : kOutOfRange;
+                // the slot at stored segment cc / 4 holds the source segment that the swizzle maps there
+                int src_seg = cc >> 2;
+                if constexpr (S == 2 || S == 4 || S == 8) src_seg = kr_swizzle<S>(krow, cc >> 2);   // XOR: its own inverse
+                const int m = row0 + src_seg * 32 + (cc & 3) * 8;
+                voff[p] = (m < rows) ? (uint32_t)(((int64_t)(k_first + krow) * ld + m) * 2) : kOutOfRange;
                 tail_bit[p] = 0u;                         // k rows beyond K fail the range check
             }
         }
-        step_bytes = kmajor ? 128u : (uint32_t)(64 * ld * 2);
+        step_bytes = kmajor ? (uint32_t)(k_stride * 2) : (uint32_t)((int64_t)k_stride * ld * 2);
     }
 
     // transfer number p of the plan alone (p is a compile-time constant at every call site)
     __device__ __forceinline__ void issue_one(int p, __amdgpu_buffer_rsrc_t rsrc, unsigned char* stage, int step,
                                               uint32_t tail_mask, int wave) const
     {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * 4 + wave) * 1024), 16,
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * NW + wave) * 1024), 16,
                                                  voff[p] | (tail_bit[p] & tail_mask), (uint32_t)step * step_bytes, 0, 0);
     }
 
@@ -98,7 +125,7 @@ struct DmaPlan {
         const uint32_t soff = (uint32_t)step * step_bytes;
 #pragma unroll
         for (int p = 0; p < NV; ++p)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * 4 + wave) * 1024), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * NW + wave) * 1024), 16,
                                                      voff[p] | (tail_bit[p] & tail_mask), soff, 0, 0);
     }
 };
@@ -118,10 +145,12 @@ struct DmaPlan4 {
     uint32_t p_bytes;        // added per transfer index p (scalar)
     uint32_t step_bytes;
 
-    __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid)
+    // same signature as DmaPlan::init; only used by blocks of one group (k_first = 0, k_stride = 64)
+    __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid, int /*k_first*/,
+                                         int /*k_stride*/, int nk)
     {
         const int wave = tid >> 6, lane = tid & 63;
-        const int ktail0 = (K / 64) * 64;
+        const int ktail0 = (nk - 1) * 64;
         const int w = lane & 3;
         if (kmajor) {
             // slot = (4p + wave) * 16 + lane / 4: row = (4p + wave) * 2 + lane / 32, chunk position (lane / 4) % 8
@@ -192,12 +221,11 @@ struct FragReader {
         } else {
             constexpr int S = ROWS / 32;
             const int kr = (lane >> 2) & 3;             // k row this lane fetches for the 4x16 transpose
-            const int f = (S == 2) ? ((kr >> 1) & 1) : kr;
             x = 0;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int m = wave_row0 + t * 32 + 16 * ((lane >> 4) & 1) + (lane & 3) * 4;
-                const int seg = (m >> 5) ^ f;
+                const int seg = kr_swizzle<S>(kr, m >> 5);
                 base[t] = (uint32_t)((lhi * 8 + kr) * (ROWS * 2) + seg * 64 + (m & 31) * 2);
             }
         }
@@ -254,40 +282,63 @@ __device__ __forceinline__ void wait_fragset(FragSet<TM, TN>& f)
 #undef FLOP_FB
 }
 
-// Main loop of one output tile.  NB stage buffers in LDS are filled by
+// Shape of a block: BM x BN output tile, NB stage buffers per group, WM x WN wavefronts per group, G groups
+// that take the 64-k steps of the contraction in turn.
+template <int BM_, int BN_, int NB_, int WM_, int WN_, int G_>
+struct TileShape {
+    static constexpr int BM = BM_, BN = BN_, NB = NB_, WM = WM_, WN = WN_, G = G_;
+    static constexpr int NWG = WM * WN;                 // wavefronts per group
+    static constexpr int THREADS = 64 * NWG * G;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;  // a wavefront's part of the tile
+    static constexpr int TM = WTM / 32, TN = WTN / 32;  // in 32x32 MFMA tiles
+    // stage rows: the tile's, rounded up so that the group's wavefronts fill them with whole instructions
+    static constexpr int round_rows(int rows) { return (rows + 8 * NWG - 1) / (8 * NWG) * (8 * NWG); }
+    static constexpr int AR = round_rows(BM), BR = round_rows(BN);
+    static constexpr int A_BYTES = AR * 128, B_BYTES = BR * 128, STAGE = A_BYTES + B_BYTES;
+    static constexpr int GROUP_BYTES = NB * STAGE;
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && TM >= 1 && TN >= 1 && TM <= 2 && TN <= 2, "wave tile");
+    static_assert(THREADS <= 1024 && G >= 1, "block size");
+    static_assert(AR % 32 == 0 && BR % 32 == 0, "stage rows are whole 64-byte segments of a [k][row] stage");
+    static_assert(THREADS % (BN / 8) == 0, "the epilogue hands whole tile rows to the block's threads");
+};
+
+// Main loop of one group of wavefronts over its share of the k steps.  NB stage buffers in LDS are filled by
 // asynchronous transfers; the fragments of step s+1 are read from LDS into a
 // second register set while the matrix cores consume the set of step s, so
 // that transfers, LDS reads and MFMAs of neighbouring steps overlap:
 //   iteration s:  wait(reads of s) ; wait(transfers of s+1) ; barrier ;
 //                 issue transfers of s+NB ; issue reads of s+1 ; MFMAs of s
-template <int BM, int BN, int NB, bool AKM, bool BKM, int XFER = 16>
+// The barriers are the block's: every group executes the same sequence of them.
+template <typename SH, bool AKM, bool BKM, int XFER = 16>
 struct DmaLoop {
-    static constexpr int WTM = BM / 2, WTN = BN / 2;
-    static constexpr int TM = WTM / 32, TN = WTN / 32;
-    static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+    static constexpr int BM = SH::BM, BN = SH::BN, NB = SH::NB, TM = SH::TM, TN = SH::TN;
+    static constexpr int A_BYTES = SH::A_BYTES, STAGE = SH::STAGE;
     static_assert(XFER == 16 || XFER == 4, "transfer width");
-    using PlanA = std::conditional_t<XFER == 16, DmaPlan<BM>, DmaPlan4<BM>>;
-    using PlanB = std::conditional_t<XFER == 16, DmaPlan<BN>, DmaPlan4<BN>>;
+    static_assert(XFER == 16 || (SH::NWG == 4 && SH::G == 1 && SH::AR == BM && SH::BR == BN), "4-byte transfers: one group of four");
+    using PlanA = std::conditional_t<XFER == 16, DmaPlan<SH::AR, SH::NWG>, DmaPlan4<BM>>;
+    using PlanB = std::conditional_t<XFER == 16, DmaPlan<SH::BR, SH::NWG>, DmaPlan4<BN>>;
     static constexpr int LPS = PlanA::NV + PlanB::NV;   // transfers per thread and stage
     static_assert(NB >= 2 && NB <= 6 && (NB - 1) * LPS < 64, "vmcnt budget");
 
     __amdgpu_buffer_rsrc_t ra, rb;
     PlanA pa;
     PlanB pb;
-    FragReader<BM, TM, AKM> fa;
-    FragReader<BN, TN, BKM> fb;
-    unsigned char* smem;
+    FragReader<SH::AR, TM, AKM> fa;
+    FragReader<SH::BR, TN, BKM> fb;
+    unsigned char* smem;    // the group's stage buffers
     uint32_t smem_addr;
-    int nk, wave;
+    int nk, wave;           // steps of every group; wavefront index inside the group
     bool ktail;
-    int kfix, kfix_chunk;   // K % 8 (elements of the chunk that straddles K) and that chunk's index in the last step
+    int kfix, kfix_chunk;   // K % 8 (elements of the chunk that straddles K); that chunk's index in this group's last
+                            // step, or -1 if it lies in another group's
 
-    __device__ __forceinline__ void init(const GemmProblem& pr, unsigned char* smem_, int m0, int n0)
+    // group: index of this wavefront's group; smem_: start of the block's dynamic LDS
+    __device__ __forceinline__ void init(const GemmProblem& pr, unsigned char* smem_, int m0, int n0, int group)
     {
-        const int tid = threadIdx.x;
+        const int tid = threadIdx.x % (64 * SH::NWG);
         const int lane = tid & 63;
         wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS targets of the transfers scalar
-        const int wm = wave >> 1, wn = wave & 1;
+        const int wm = wave / SH::WN, wn = wave % SH::WN;
         // whole transfers: the last 16-byte chunk (4-byte word) of a row may reach into the row's padding
         constexpr int E = XFER / 2;
         const int64_t K8 = (pr.K + E - 1) & ~(E - 1), M8 = (pr.M + E - 1) & ~(E - 1), N8 = (pr.N + E - 1) & ~(E - 1);
@@ -300,16 +351,22 @@ struct DmaLoop {
         const uint16_t* b_base = (const uint16_t*)pr.B + (BKM ? (int64_t)n0 * pr.ldb : 0);
         ra = __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, (int)(a_elems * 2), 0x00020000);
         rb = __builtin_amdgcn_make_buffer_rsrc((void*)b_base, 0, (int)(b_elems * 2), 0x00020000);
-        pa.init(AKM, pr.lda, AKM ? 0 : m0, AKM ? pr.M - m0 : pr.M, pr.K, tid);
-        pb.init(BKM, pr.ldb, BKM ? 0 : n0, BKM ? pr.N - n0 : pr.N, pr.K, tid);
-        fa.init(wm * WTM, lane);
-        fb.init(wn * WTN, lane);
-        smem = smem_;
-        smem_addr = (uint32_t)(uintptr_t)FLOP_LDS_PTR(smem_);
-        nk = (pr.K + 63) / 64;
-        ktail = (pr.K & 63) != 0;
+        constexpr int KS = 64 * SH::G;
+        nk = (pr.K + KS - 1) / KS;
+        const int k_first = 64 * group;
+        // rows of a [row][k] operand beyond the tile (stage rows that only pad the tile included) lie beyond the
+        // descriptor; of a [k][row] operand they are tested against the matrix
+        pa.init(AKM, pr.lda, AKM ? 0 : m0, AKM ? min(BM, pr.M - m0) : min(pr.M, m0 + BM), pr.K, tid, k_first, KS, nk);
+        pb.init(BKM, pr.ldb, BKM ? 0 : n0, BKM ? min(BN, pr.N - n0) : min(pr.N, n0 + BN), pr.K, tid, k_first, KS, nk);
+        fa.init(wm * SH::WTM, lane);
+        fb.init(wn * SH::WTN, lane);
+        smem = smem_ + group * SH::GROUP_BYTES;
+        smem_addr = (uint32_t)(uintptr_t)FLOP_LDS_PTR(smem);
+        const int last0 = (nk - 1) * KS + k_first;          // first k of this group's last step
+        ktail = last0 + 64 > pr.K;
         kfix = pr.K & 7;
-        kfix_chunk = (pr.K & 63) >> 3;
+        const int straddle = pr.K & ~7;                     // first k of the chunk that straddles K
+        kfix_chunk = (straddle >= last0 && straddle < last0 + 64) ? ((straddle - last0) >> 3) : -1;
     }
 
     __device__ __forceinline__ void issue(int step) const
@@ -334,22 +391,25 @@ struct DmaLoop {
     // K not a multiple of 8: in the last step the chunk that straddles K has brought
     // elements of the row padding into the k-major stage buffers; clear them (an
     // operand stored [k][row] needs nothing: its rows beyond K fail the range check).
-    // Call with the stage landed and a barrier passed; block-uniform.
+    // Call with the stage landed and a barrier passed; the condition is the same for every
+    // group of the block (they all reach the barrier inside), only the chunk's owner writes.
     __device__ __forceinline__ void fix_ktail(int step) const
     {
         if (kfix == 0 || step != nk - 1) return;
         unsigned char* st = smem + (step % NB) * STAGE;
-        const int tid = threadIdx.x;
-        if constexpr (AKM)
-            for (int row = tid; row < BM; row += kGemmThreads) {
-                uint16_t* c = (uint16_t*)(st + row * 128 + ((kfix_chunk ^ ((row >> 1) & 7)) << 4));
-                for (int e = kfix; e < 8; ++e) c[e] = 0;
-            }
-        if constexpr (BKM)
-            for (int row = tid; row < BN; row += kGemmThreads) {
-                uint16_t* c = (uint16_t*)(st + A_BYTES + row * 128 + ((kfix_chunk ^ ((row >> 1) & 7)) << 4));
-                for (int e = kfix; e < 8; ++e) c[e] = 0;
-            }
+        const int tid = threadIdx.x % (64 * SH::NWG);
+        if (kfix_chunk >= 0) {
+            if constexpr (AKM)
+                for (int row = tid; row < BM; row += 64 * SH::NWG) {
+                    uint16_t* c = (uint16_t*)(st + row * 128 + ((kfix_chunk ^ ((row >> 1) & 7)) << 4));
+                    for (int e = kfix; e < 8; ++e) c[e] = 0;
+                }
+            if constexpr (BKM)
+                for (int row = tid; row < BN; row += 64 * SH::NWG) {
+                    uint16_t* c = (uint16_t*)(st + A_BYTES + row * 128 + ((kfix_chunk ^ ((row >> 1) & 7)) << 4));
+                    for (int e = kfix; e < 8; ++e) c[e] = 0;
+                }
+        }
         __syncthreads();
     }
 
@@ -479,24 +539,26 @@ struct DmaLoop {
     }
 };
 
-template <int BM, int BN, int NB, bool AKM, bool BKM, int XFER>
-__device__ __forceinline__ void dma_main_loop(const GemmProblem& pr, unsigned char* smem, int m0, int n0,
-                                              f32x16 (&acc)[BM / 64][BN / 64])
+template <typename SH, bool AKM, bool BKM, int XFER>
+__device__ __forceinline__ void dma_main_loop(const GemmProblem& pr, unsigned char* smem, int m0, int n0, int group,
+                                              f32x16 (&acc)[SH::TM][SH::TN])
 {
-    DmaLoop<BM, BN, NB, AKM, BKM, XFER> loop;
-    loop.init(pr, smem, m0, n0);
+    DmaLoop<SH, AKM, BKM, XFER> loop;
+    loop.init(pr, smem, m0, n0, group);
     loop.run(acc);
 }
 
-template <int BM, int BN, int NSTAGE, bool BKM, int XFER = 16>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmGroup grp)
+template <typename SH, bool BKM, int XFER = 16>
+__global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(const GemmGroup grp)
 {
-    constexpr int WTM = BM / 2, WTN = BN / 2;
-    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int BM = SH::BM, BN = SH::BN, TM = SH::TM, TN = SH::TN, WTM = SH::WTM, WTN = SH::WTN;
+    constexpr int THREADS = SH::THREADS, NWAVES = THREADS / 64;
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     if (grp.rider_blocks > 0 && (int)blockIdx.x >= grp.tile_blocks) {   // block-uniform
+        // the step-boundary blocks are written for kStreamThreads threads; surplus wavefronts leave
+        if (THREADS > kStreamThreads && (int)threadIdx.x >= kStreamThreads) return;
         const int id = (int)blockIdx.x - grp.tile_blocks;
         step_boundary_block(grp.rider.fb, grp.rider.count, grp.rider.gj, id % grp.rider.bx, id / grp.rider.bx);
         return;
@@ -508,7 +570,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmG
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int group = __builtin_amdgcn_readfirstlane(wave / SH::NWG);
+    const int wig = wave % SH::NWG;                       // wavefront inside its group
+    const int wm = wig / SH::WN, wn = wig % SH::WN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
     f32x16 acc[TM][TN];
@@ -519,22 +583,54 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmG
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    if (pr.a_kmajor) dma_main_loop<BM, BN, NSTAGE, true, BKM, XFER>(pr, smem, m0, n0, acc);
-    else dma_main_loop<BM, BN, NSTAGE, false, BKM, XFER>(pr, smem, m0, n0, acc);
+    if (pr.a_kmajor) dma_main_loop<SH, true, BKM, XFER>(pr, smem, m0, n0, group, acc);
+    else dma_main_loop<SH, false, BKM, XFER>(pr, smem, m0, n0, group, acc);
     __syncthreads();
 
-    // ---- k-split launch: this block's float32 partial sums, unscaled; a later kernel adds the slices
-    if (pr.ksplit > 1) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * WTN + j * 32 + l32;
+    // ---- the groups' partial sums are added in group order (fixed, so the result is deterministic): groups
+    // 1 .. G-1 leave theirs in LDS, lane-interleaved, group 0 adds them up and goes on alone
+    if constexpr (SH::G > 1) {
+        float* part = (float*)smem;
+        constexpr int PER_WAVE = TM * TN * 16 * 64;      // floats a wavefront holds
+        if (group > 0) {
+            float* mine = part + ((group - 1) * SH::NWG + wig) * PER_WAVE + lane;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                    if (row < pr.M && col < pr.N) pr.split_out[(int64_t)row * pr.N + col] = acc[i][j][v];
-                }
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mine[((i * TN + j) * 16 + v) * 64] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (group == 0) {
+#pragma unroll
+            for (int gg = 1; gg < SH::G; ++gg) {
+                const float* theirs = part + ((gg - 1) * SH::NWG + wig) * PER_WAVE + lane;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] += theirs[((i * TN + j) * 16 + v) * 64];
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- k-split launch: this block's float32 partial sums, unscaled; a later kernel adds the slices
+    if (pr.ksplit > 1) {
+        if (group == 0) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * WTN + j * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                        if (row < pr.M && col < pr.N) pr.split_out[(int64_t)row * pr.N + col] = acc[i][j][v];
+                    }
+            }
         }
         return;
     }
@@ -542,19 +638,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmG
     // ---- epilogue ------------------------------------------------------------------
     // Output tile: gate scale, one rounding to bfloat16, staged in LDS as [row][col]
     // (rows padded by 16 bytes), then written with 16-byte row-contiguous stores.
-    // A thread owns chunk column cc of the rows row_t, row_t + RSTEP, ...; with
-    // pr.dot it also adds up C .* dot over those rows for its 8 columns.
+    // The first ACTIVE threads each own chunk column cc of the rows row_t, row_t + RSTEP, ...; with
+    // pr.dot they also add up C .* dot over those rows for their 8 columns.
     constexpr int PITCH = BN * 2 + 16;
     constexpr int CPR = BN / 8;                    // 16-byte chunks per tile row
-    constexpr int RSTEP = kGemmThreads / CPR;      // rows between two chunks of a thread
-    constexpr int NCH = BM / RSTEP;                // chunks per thread
-    static_assert(kGemmThreads % CPR == 0 && BM % RSTEP == 0, "chunk ownership");
+    constexpr int RSTEP_MAX = THREADS / CPR;       // rows that the block's threads cover in one pass
+    constexpr int RSTEP = (BM % RSTEP_MAX == 0) ? RSTEP_MAX : (BM % (RSTEP_MAX / 2) == 0 ? RSTEP_MAX / 2 : RSTEP_MAX / 4);
+    constexpr int ACTIVE = RSTEP * CPR;            // threads that store (all of them unless BN / 8 does not divide the block)
+    constexpr int NCH = BM / RSTEP;                // chunks per storing thread
+    static_assert(RSTEP >= 1 && BM % RSTEP == 0 && ACTIVE <= THREADS, "chunk ownership");
+    const bool storing = tid < ACTIVE;
     const int cc = tid % CPR, row_t = tid / CPR;
     const int ccol = n0 + cc * 8;
     const bool dot = pr.dot_partial != nullptr;
     const bool dot_vec = (((uintptr_t)pr.dot & 15u) == 0) && (pr.lddot % 8 == 0);
     u32x4 gq[NCH];
-    if (dot) {
+    if (dot && storing) {
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
             const int row = m0 + row_t + q * RSTEP;
@@ -573,26 +672,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmG
             }
         }
     }
+    if (group == 0) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col_l = wn * WTN + j * 32 + l32;
-        const int col = n0 + col_l;
-        float scale = 1.0f;
-        if (col < pr.N) {
-            if (pr.gate_alpha) {   // the gate itself, bit for bit what the gate kernels write for the same inputs
-                float dd;
-                gate_one(pr.gate_alpha[col], pr.gate_u[col], 1.0f / pr.gate_beta, pr.gate_l, pr.gate_r, 0, scale, dd);
-            } else if (pr.col_scale) {
-                scale = pr.col_scale[col];
+        for (int j = 0; j < TN; ++j) {
+            const int col_l = wn * WTN + j * 32 + l32;
+            const int col = n0 + col_l;
+            float scale = 1.0f;
+            if (col < pr.N) {
+                if (pr.gate_alpha) {   // the gate itself, bit for bit what the gate kernels write for the same inputs
+                    float dd;
+                    gate_one(pr.gate_alpha[col], pr.gate_u[col], 1.0f / pr.gate_beta, pr.gate_l, pr.gate_r, 0, scale, dd);
+                } else if (pr.col_scale) {
+                    scale = pr.col_scale[col];
+                }
             }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row_l = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                    *(uint16_t*)(smem + row_l * PITCH + col_l * 2) = (uint16_t)f32_to_bf16_bits(acc[i][j][v] * scale);
+                }
         }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row_l = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                *(uint16_t*)(smem + row_l * PITCH + col_l * 2) = (uint16_t)f32_to_bf16_bits(acc[i][j][v] * scale);
-            }
     }
     __syncthreads();
     const bool c_vec = (((uintptr_t)pr.C & 15u) == 0) && (pr.ldc % 8 == 0);
@@ -600,59 +701,63 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmG
     float ds[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) ds[e] = 0.0f;
+    if (storing) {
 #pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-        const int row_l = row_t + q * RSTEP;
-        const int row = m0 + row_l;
-        if (row >= pr.M || ccol >= pr.N) continue;
-        const u32x4 v = *(const u32x4*)(smem + row_l * PITCH + cc * 16);
-        const int64_t orow = pr.c_rowmap ? pr.c_rowmap[row] : row;
-        uint16_t* dst = (uint16_t*)pr.C + orow * pr.ldc + ccol;
-        if (c_vec && ccol + 8 <= pr.N) {
-            *(u32x4*)dst = v;
-        } else if (c_word && ccol + 8 <= pr.N) {
-            ((uint32_t*)dst)[0] = v[0]; ((uint32_t*)dst)[1] = v[1];
-            ((uint32_t*)dst)[2] = v[2]; ((uint32_t*)dst)[3] = v[3];
-        } else {
+        for (int q = 0; q < NCH; ++q) {
+            const int row_l = row_t + q * RSTEP;
+            const int row = m0 + row_l;
+            if (row >= pr.M || ccol >= pr.N) continue;
+            const u32x4 v = *(const u32x4*)(smem + row_l * PITCH + cc * 16);
+            const int64_t orow = pr.c_rowmap ? pr.c_rowmap[row] : row;
+            uint16_t* dst = (uint16_t*)pr.C + orow * pr.ldc + ccol;
+            if (c_vec && ccol + 8 <= pr.N) {
+                *(u32x4*)dst = v;
+            } else if (c_word && ccol + 8 <= pr.N) {
+                ((uint32_t*)dst)[0] = v[0]; ((uint32_t*)dst)[1] = v[1];
+                ((uint32_t*)dst)[2] = v[2]; ((uint32_t*)dst)[3] = v[3];
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (ccol + e < pr.N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
-        }
-        if (dot) {
+                for (int e = 0; e < 8; ++e)
+                    if (ccol + e < pr.N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
+            }
+            if (dot) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t vw = v[e >> 1], gw = gq[q][e >> 1];
-                const float cv = __builtin_bit_cast(float, (e & 1) ? (vw & 0xFFFF0000u) : (vw << 16));
-                const float gv = __builtin_bit_cast(float, (e & 1) ? (gw & 0xFFFF0000u) : (gw << 16));
-                if (ccol + e < pr.N) ds[e] = fmaf(cv, gv, ds[e]);
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t vw = v[e >> 1], gw = gq[q][e >> 1];
+                    const float cv = __builtin_bit_cast(float, (e & 1) ? (vw & 0xFFFF0000u) : (vw << 16));
+                    const float gv = __builtin_bit_cast(float, (e & 1) ? (gw & 0xFFFF0000u) : (gw << 16));
+                    if (ccol + e < pr.N) ds[e] = fmaf(cv, gv, ds[e]);
+                }
             }
         }
     }
     if (dot) {
-        // threads cc, cc + CPR, ... of a wave hold the same columns: butterfly over them,
-        // then the four waves are added in a fixed order through LDS
+        // Column sums of the tile: every thread leaves its eight in LDS (threads that stored nothing leave
+        // zeros), then thread n adds column n over the RSTEP row lanes in a fixed order.
         float* red = (float*)(smem + ((BM * PITCH + 15) & ~15));
+        if (storing) {
 #pragma unroll
-        for (int off = CPR; off < 64; off <<= 1)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) ds[e] += __shfl_xor(ds[e], off);
-        if (lane < CPR) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) red[wave * BN + lane * 8 + e] = ds[e];
+            for (int e = 0; e < 8; ++e) red[row_t * BN + cc * 8 + e] = ds[e];
         }
         __syncthreads();
-        if (tid < BN && n0 + tid < pr.N)
-            pr.dot_partial[(int64_t)tile_m * pr.dot_ld + n0 + tid] =
-                (red[tid] + red[BN + tid]) + (red[2 * BN + tid] + red[3 * BN + tid]);
+        if (tid < BN && n0 + tid < pr.N) {
+            float tot = 0.0f;
+#pragma unroll 8
+            for (int q = 0; q < RSTEP; ++q) tot += red[q * BN + tid];
+            pr.dot_partial[(int64_t)tile_m * pr.dot_ld + n0 + tid] = tot;
+        }
     }
 }
 
-template <int BM, int BN, int NSTAGE>
+template <typename SH>
 constexpr size_t gemm_dma_lds_bytes()
 {
-    const size_t stages = (size_t)NSTAGE * (BM + BN) * 128;
-    const size_t out_tile = (size_t)BM * (BN * 2 + 16) + 16 + 4 * BN * sizeof(float);   // + per-wave column sums
-    return stages > out_tile ? stages : out_tile;
+    constexpr int THREADS = SH::THREADS, CPR = SH::BN / 8, RSTEP_MAX = THREADS / CPR;
+    const size_t stages = (size_t)SH::G * SH::GROUP_BYTES;
+    const size_t partials = (size_t)(SH::G - 1) * SH::BM * SH::BN * sizeof(float);
+    const size_t out_tile = (size_t)SH::BM * (SH::BN * 2 + 16) + 16 + (size_t)RSTEP_MAX * SH::BN * sizeof(float);   // + column-sum lanes
+    size_t m = stages > out_tile ? stages : out_tile;
+    return m > partials ? m : partials;
 }
 
 }  // namespace flop

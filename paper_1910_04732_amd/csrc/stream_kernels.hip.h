@@ -98,10 +98,10 @@ __global__ __launch_bounds__(kStreamThreads) void gate_sample_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Block-wide sum of one double per thread (wave shuffles, then LDS).
-// Result valid in thread 0.
+// Sum of one double per thread over the first `waves` wavefronts of the block (wave shuffles, then
+// LDS); every one of them calls, none of the others does.  Result valid in thread 0.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ double block_sum(double v, double* lds /* >= 4 doubles */)
+__device__ __forceinline__ double block_sum(double v, double* lds /* >= waves doubles */, int waves)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
@@ -110,7 +110,7 @@ __device__ __forceinline__ double block_sum(double v, double* lds /* >= 4 double
     __syncthreads();
     double tot = 0.0;
     if (threadIdx.x == 0)
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += lds[w];
+        for (int w = 0; w < waves; ++w) tot += lds[w];
     return tot;
 }
 
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kStreamThreads) void expected_l0_kernel(
             if (grad) grad[k + e] = g;
         }
     }
-    const double tot = block_sum(acc, lds);
+    const double tot = block_sum(acc, lds, kStreamThreads / 64);
     if (threadIdx.x == 0) {
         if (gridDim.x == 1) out[0] = (float)tot;
         else block_sums[blockIdx.x] = tot;
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kStreamThreads) void expected_l0_finish_kernel(
     __shared__ double lds[kStreamThreads / 64];
     double acc = 0.0;
     for (int i = threadIdx.x; i < nblocks; i += kStreamThreads) acc += block_sums[i];
-    const double tot = block_sum(acc, lds);
+    const double tot = block_sum(acc, lds, kStreamThreads / 64);
     if (threadIdx.x == 0) out[0] = (float)tot;
 }
 
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kGateL0Threads) void gate_l0_kernel(
         if (l0_grad) l0_grad[k] = ww * p * (e * p);
         acc += (double)(ww * p);
     }
-    const double tot = block_sum(acc, lds);
+    const double tot = block_sum(acc, lds, kGateL0Threads / 64);
     if (threadIdx.x == 0) l0_sum[0] = (float)tot;
 }
 
@@ -399,7 +399,7 @@ __device__ __forceinline__ void step_boundary_block(const FinishBatch& b, const 
         if (gj.l0_grad) gj.l0_grad[k] = ww * p * (e * p);
         acc += (double)(ww * p);
     }
-    const double tot = block_sum(acc, lds);
+    const double tot = block_sum(acc, lds, kStreamThreads / 64);   // the block may have more wavefronts: they are not here
     if (threadIdx.x == 0) gj.l0_sum[0] = (float)tot;
 }
 
@@ -416,46 +416,6 @@ struct BoundaryRider {
     int count;
     int bx;        // blocks per gate vector: ceil(largest r / 32)
 };
-
-// ---------------------------------------------------------------------------
-// Matrix-core rate probe (measurement aid, no part of the method): every wave issues
-// `iters` rounds of four independent 32x32 MFMAs on register operands, nothing else; the
-// accumulators are folded into `sink` so the loop cannot be dropped.  The contraction kernels' rate is
-// quoted against what this reaches as well as against the datasheet figure.
-// ---------------------------------------------------------------------------
-constexpr int kProbeWavesPerBlock = 4;
-constexpr int kProbeChains = 4;
-
-template <bool BF16>
-__global__ __launch_bounds__(64 * kProbeWavesPerBlock) void mfma_probe_kernel(int iters, float* __restrict__ sink)
-{
-    typedef float acc16 __attribute__((ext_vector_type(16)));
-    typedef __bf16 op8 __attribute__((ext_vector_type(8)));
-    acc16 acc[kProbeChains];
-#pragma unroll
-    for (int c = 0; c < kProbeChains; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[c][e] = 0.0f;
-    // operands small enough that no accumulator leaves the normal range
-    const float seed = 1.0f / (float)(1 + (threadIdx.x & 7));
-    op8 a, b;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(seed * 0.001f); b[e] = (__bf16)(0.5f - seed); }
-    const float af = seed * 0.001f, bf = 0.5f - seed;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int c = 0; c < kProbeChains; ++c) {
-            if constexpr (BF16) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
-            else                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc[c], 0, 0, 0);
-        }
-    }
-    float tot = 0.0f;
-#pragma unroll
-    for (int c = 0; c < kProbeChains; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) tot += acc[c][e];
-    if (blockIdx.x == 0 && threadIdx.x < 64) sink[threadIdx.x] = tot;
-}
 
 // ---------------------------------------------------------------------------
 // Compaction (Sections 4.1 / 4.4): keep k iff z[k] > 0, ascending order.

@@ -120,6 +120,11 @@ def lib():
         L.flop_active_prepare.restype = _int
         for name in ("flop_fwd_active", "flop_bwd_active", "flop_gather_gates", "flop_expand_grads"):
             getattr(L, name).restype = _int
+        L.flop_bench_force_tile_shape.argtypes = [_int]
+        L.flop_bench_force_tile_shape.restype = _int
+        L.flop_bench_tile_shapes.restype = _int
+        L.flop_bench_tile_shape_name.argtypes = [_int]
+        L.flop_bench_tile_shape_name.restype = ctypes.c_char_p
         L.flop_trace_begin.argtypes = [_int]
         L.flop_trace_end.argtypes = [ctypes.POINTER(flop_trace_record), _int, ctypes.POINTER(_int)]
         for name in ("flop_trace_begin", "flop_trace_end", "flop_gate_sample", "flop_fwd", "flop_bwd", "flop_expected_l0", "flop_compact"):
@@ -478,6 +483,16 @@ def flop_compact(z, Q, P, r_out, idx, Qc=None, Pc=None, zc=None, absorb_z_into_Q
                               qcp, ldqc, pcp, ldpc, _vec(zc, "zc"),
                               _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)), "flop_compact")
     return r_out, idx
+
+
+def flop_bench_force_tile_shape(shape: int):
+    """Test/benchmark aid: every following bf16 transfer-kernel launch uses block shape ``shape`` (-1: automatic)."""
+    _check(lib().flop_bench_force_tile_shape(int(shape)), "flop_bench_force_tile_shape")
+
+
+def flop_bench_tile_shapes():
+    """Names of the block shapes, indexed by shape number."""
+    return [lib().flop_bench_tile_shape_name(i).decode() for i in range(lib().flop_bench_tile_shapes())]
 
 
 def flop_trace_begin(capacity: int):

@@ -10,10 +10,11 @@
 //                                           (odd, 2 mod 4, 4 mod 8, 0 mod 8) with dense last rows, riders on
 //                                           and off, empty pending lists, boundary jobs with and without new gates
 //
-//   address_model case <bf16|f32> <extra> n d r dout [n d r dout ...]   the given layers, with and without new gates
+//   address_model case <bf16|f32> <extra> n d r dout [n d r dout ...]   the given layers, with and without new gates, every block shape
 //
 // Prints one line per case before running it, so that a report names its case.
 #include "../../paper_1910_04732_amd/csrc/flop_api.hip"
+#include "../../paper_1910_04732_amd/csrc/flop_bench.hip"
 
 #include <random>
 #include <string>
@@ -177,7 +178,9 @@ int run_random(uint64_t seed, int cases)
         static const int64_t extras[4] = {0, 0, 3000, 5000};
         const int64_t extra = rng.pick(extras);
         const bool next_gates = rng.uni() < 0.3;
-        printf("case %d %s\n", c, describe(dt, shapes, extra, next_gates).c_str());
+        const int shape = (int)rng.range(-1, flop_bench_tile_shapes());   // block shape of the bf16 transfer kernel
+        must(flop_bench_force_tile_shape(shape), "flop_bench_force_tile_shape");
+        printf("case %d %s shape %s\n", c, describe(dt, shapes, extra, next_gates).c_str(), flop_bench_tile_shape_name(shape));
         fflush(stdout);
         run_case(dt, shapes, extra, next_gates);
     }
@@ -198,7 +201,10 @@ int run_classes(int stride)
                 const int64_t n = ns[c % 6];
                 const std::vector<std::array<int64_t, 4>> one = {{n, d, r, dout}};
                 const std::vector<std::array<int64_t, 4>> two = {{n, d, r, dout}, {ns[(c + 1) % 6], dout, r, d}};
-                printf("class %d %s\n", c, describe(FLOP_BF16, c % 3 ? one : two, c % 5 ? 0 : 37, c % 2).c_str());
+                const int shape = (c / stride) % (flop_bench_tile_shapes() + 1) - 1;
+                must(flop_bench_force_tile_shape(shape), "flop_bench_force_tile_shape");
+                printf("class %d %s shape %s\n", c, describe(FLOP_BF16, c % 3 ? one : two, c % 5 ? 0 : 37, c % 2).c_str(),
+                       flop_bench_tile_shape_name(shape));
                 fflush(stdout);
                 run_case(FLOP_BF16, c % 3 ? one : two, c % 5 ? 0 : 37, c % 2);
                 ++c;
@@ -217,11 +223,13 @@ int main(int argc, char** argv)
         std::vector<std::array<int64_t, 4>> shapes;
         for (int i = 4; i + 3 < argc; i += 4) shapes.push_back({atoll(argv[i]), atoll(argv[i + 1]), atoll(argv[i + 2]), atoll(argv[i + 3])});
         const flop_dtype dt = !strcmp(argv[2], "f32") ? FLOP_F32 : FLOP_BF16;
-        for (int next = 0; next < 2; ++next) {
-            printf("case %s\n", describe(dt, shapes, atoll(argv[3]), next != 0).c_str());
-            fflush(stdout);
-            run_case(dt, shapes, atoll(argv[3]), next != 0);
-        }
+        for (int shape = -1; shape < flop_bench_tile_shapes(); ++shape)
+            for (int next = 0; next < 2; ++next) {
+                must(flop_bench_force_tile_shape(shape), "flop_bench_force_tile_shape");
+                printf("case %s shape %s\n", describe(dt, shapes, atoll(argv[3]), next != 0).c_str(), flop_bench_tile_shape_name(shape));
+                fflush(stdout);
+                run_case(dt, shapes, atoll(argv[3]), next != 0);
+            }
         rc = 0;
     }
     else fprintf(stderr, "usage: address_model random <seed> <cases> | classes [stride] | case <bf16|f32> <extra gates> n d r dout ...\n");

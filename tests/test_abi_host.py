@@ -12,9 +12,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "flop.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(flop_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("flop.h", "flop_bench.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(flop_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 @pytest.fixture(scope="module")
@@ -28,9 +31,9 @@ def lib():
 def test_header_symbols_are_exported(lib):
     names = _declared()
     assert {"flop_gate_sample", "flop_fwd", "flop_bwd", "flop_expected_l0", "flop_compact",
-            "flop_workspace_bytes", "flop_status_string"} <= set(names)
+            "flop_workspace_bytes", "flop_status_string", "flop_bwd_static", "flop_bench_force_tile_shape"} <= set(names)
     for name in names:
-        assert hasattr(lib, name), f"{name} declared in include/flop.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/*.h but not exported"
 
 
 def test_status_strings(lib):
