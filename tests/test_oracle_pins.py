@@ -47,6 +47,10 @@ def test_golden_points():
             l, r, alpha, z_exp = vals
             z, _ = oracle.gate_sample([alpha], None, 1.0, l, r, deterministic=True)
             assert z[0] == pytest.approx(z_exp, abs=1e-6)
+        elif kind == "gate_det_grad":
+            beta, l, r, alpha, d_exp = vals
+            _, dzda = oracle.gate_sample([alpha], None, beta, l, r, deterministic=True)
+            assert dzda[0] == pytest.approx(d_exp, abs=1e-12)
         elif kind == "l0":
             beta, l, r, alpha, count, s_exp = vals
             s, _ = oracle.expected_l0(np.full(int(count), alpha), beta, l, r)
@@ -98,6 +102,36 @@ def test_deterministic_gate():
     thr = math.log(-L / R)
     z, _ = oracle.gate_sample([thr - 1e-9, thr + 1e-9, 0.0, 30.0], None, BETA, L, R, deterministic=True)
     assert z[0] == 0.0 and z[1] > 0.0 and z[2] == pytest.approx(0.5) and z[3] == 1.0
+
+
+def test_deterministic_gate_gradient():
+    """dz/dalpha of the deterministic gate z = clamp(sigmoid(alpha)(r - l) + l): no temperature in it, so it is
+    (r - l) s (1 - s) whatever beta is, zero outside the clamp, and the slope of z itself."""
+    a = np.array([-2.0, -1.0, -0.3, 0.0, 0.4, 1.0986122886681098, 2.0])       # all strictly inside the clamp
+    for beta in (1.0, 2.0 / 3.0, 0.25):
+        z, dzda = oracle.gate_sample(a, None, beta, L, R, deterministic=True)
+        assert np.all((z > 0) & (z < 1))
+        s = 1.0 / (1.0 + np.exp(-a))
+        np.testing.assert_allclose(dzda, (R - L) * s * (1 - s), rtol=1e-13)
+        h = 1e-6
+        zp, _ = oracle.gate_sample(a + h, None, beta, L, R, deterministic=True)
+        zm, _ = oracle.gate_sample(a - h, None, beta, L, R, deterministic=True)
+        np.testing.assert_allclose(dzda, (zp - zm) / (2 * h), rtol=1e-8)
+    # beta does enter the training mode: the two modes differ by exactly 1/beta at u = 1/2
+    _, d_train = oracle.gate_sample([0.0], [0.5], 0.25, L, R)
+    _, d_det = oracle.gate_sample([0.0], None, 0.25, L, R, deterministic=True)
+    assert d_train[0] == pytest.approx(4.0 * d_det[0], rel=1e-14)
+    # closed and saturated gates pass no gradient
+    _, dz = oracle.gate_sample([math.log(-L / R) - 0.5, math.log((1 - L) / (R - 1)) + 0.5], None, BETA, L, R,
+                               deterministic=True)
+    assert dz[0] == 0.0 and dz[1] == 0.0
+
+
+def test_noise_at_the_ends_of_its_range():
+    """u = 0 and u = 1 (outside the open interval the workloads draw from): log u - log(1 - u) is -inf / +inf,
+    so the gate is closed / saturated whatever alpha is, with zero slope and no NaN."""
+    z, dzda = oracle.gate_sample([-3.0, 0.0, 25.0, -25.0, 0.0, 3.0], [0.0, 0.0, 0.0, 1.0, 1.0, 1.0], BETA, L, R)
+    assert z.tolist() == [0.0, 0.0, 0.0, 1.0, 1.0, 1.0] and dzda.tolist() == [0.0] * 6
 
 
 @pytest.mark.parametrize("beta,alpha", [(1.0, 0.0), (2.0 / 3.0, 0.0), (2.0 / 3.0, -1.3), (0.5, 0.8)])
