@@ -154,11 +154,10 @@ using Shape64x96g2n2 = TileShape<64, 96, 2, 2, 3, 2>;     // 96 KB, 768 threads
 using Shape128x64g2n2 = TileShape<128, 64, 2, 2, 2, 2>;   // 96 KB, 512 threads
 using Shape64x64n2 = TileShape<64, 64, 2, 2, 2, 1>;       // 32 KB, five blocks per compute unit
 constexpr int kNumShapes = kNumTileShapes;
-struct ShapeInfo { int bm, bn, groups, blocks_per_cu; double step_us; };   // step_us: one 64-k step of a group
+struct ShapeInfo { int bm, bn, groups; };
 constexpr ShapeInfo kShapes[kNumShapes] = {
-    {128, 128, 1, 2, 0.82}, {128, 64, 1, 2, 0.59}, {64, 64, 1, 3, 0.43}, {64, 64, 2, 1, 0.45}, {64, 96, 2, 1, 0.50},
-    {128, 64, 2, 1, 0.62}, {128, 128, 2, 1, 0.85}, {256, 128, 1, 1, 1.10}, {64, 64, 4, 1, 0.50}, {64, 96, 1, 2, 0.50},
-    {64, 64, 2, 2, 0.45}, {64, 96, 2, 1, 0.50}, {128, 64, 2, 1, 0.62}, {64, 64, 1, 5, 0.43},
+    {128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 64, 2}, {64, 96, 2}, {128, 64, 2}, {128, 128, 2},
+    {256, 128, 1}, {64, 64, 4}, {64, 96, 1}, {64, 64, 2}, {64, 96, 2}, {128, 64, 2}, {64, 64, 1},
 };
 
 template <typename SH, bool BKM, int XFER>
@@ -236,71 +235,107 @@ inline int plan_ksplit(int64_t M, int64_t N, int64_t K)
     return s < 2 ? 1 : (int)s;
 }
 
-// Tile shape for a launch of the bf16 transfer kernel: 0 = 128x128, 1 = 128x64, 2 = 64x64, whichever a small
-// timing model of the launch puts first.  The model: a tile takes steps x step_us (measured per-step times of the
-// three shapes when operands arrive from L2: the larger the tile, the longer a step and the fewer steps in flight
-// per CU); the chip holds 256 x occupancy tiles at once and takes the rest as slots free up (tiles ordered by k
-// extent, as the kernel numbers them); and the launch cannot beat the rate at which CUs take operands in
-// (stage bytes per tile step over ~20 TB/s).  What it decides in practice: one round of large tiles beats two
-// rounds of smaller ones, and a product with few tiles and a long k extent wants small tiles, because its tiles
-// are the critical path of the launch.
-inline int pick_cfg(const GemmDesc* d, int count, bool transfer_kernel)
+// Block shape for a launch.  Generic kernel (xfer == 0): 128x128 (0) when that still gives every compute unit
+// work, else 64x64 (2).  bf16 transfer kernel: whichever candidate a small timing model of the launch puts
+// first.  The model follows one compute unit: tiles are numbered by decreasing k extent (as the kernel numbers
+// them) and dealt to the 256 units in turn; a unit runs up to `occ` blocks at once; a block advances one 64-k
+// step (of each of its k groups) in max(lat_us, bytes staged per step by the unit's running blocks / intake rate)
+// and pays tile_us once for its first load and its output store.  The intake rate (100 KB/us per unit) and the
+// per-shape constants were fitted to per-launch times of the eight launches of the BERT-shaped step measured
+// with every shape forced in turn; what the model decides in practice: one round of large tiles beats two
+// rounds of smaller ones, a product with few tiles and a long k extent wants small tiles or k groups, launches
+// of many rounds want the largest tile.
+struct ShapeModel { int cfg, bm, bn, groups, occ; double lat_us, tile_us; };
+constexpr ShapeModel kShapeModels[] = {
+    {2, 64, 64, 1, 3, 0.12, 0.5},   {9, 64, 96, 1, 2, 0.24, 2.5},   {4, 64, 96, 2, 1, 0.40, 3.5},
+    {1, 128, 64, 1, 2, 0.32, 1.5},  {0, 128, 128, 1, 2, 0.56, 4.0}, {7, 256, 128, 1, 1, 0.54, 5.5},
+};
+constexpr double kIntakeKBPerUs = 100.0;
+
+inline double model_launch_us(const ShapeModel& sm, const GemmDesc* d, const int* order, int count)
 {
-    if (transfer_kernel && forced_tile_shape() >= 0) return forced_tile_shape();   // flop_bench.h
-    bool narrow = true;   // no product wider than 64 columns: 128-wide tiles would be half empty
+    const double stage_kb = (double)(sm.bm + sm.bn) * 128.0 * sm.groups / 1024.0;
+    const double tile_steps = sm.tile_us / sm.lat_us;
+    double active[8];
+    int nactive = 0;
+    double t = 0.0;
+    int oi = 0;
+    int64_t index = 0, prod_end = 0, next_mine = 0;   // global tile index; unit 0 owns every 256th tile
+    double prod_steps = 0.0;
+    bool more = true;
+    while (more || nactive > 0) {
+        while (nactive < sm.occ && more) {
+            // advance to the product that holds tile next_mine
+            while (next_mine >= prod_end) {
+                if (oi >= count) { more = false; break; }
+                const GemmDesc& g = d[order[oi++]];
+                if (g.M <= 0 || g.N <= 0) continue;
+                const int slices = (g.seg || g.ext) ? 1 : plan_ksplit(g.M, g.N, g.K);
+                int64_t steps = (((g.K + 63) / 64) + slices - 1) / slices;
+                steps = (steps + sm.groups - 1) / sm.groups;
+                prod_steps = (double)(steps > 0 ? steps : 1) + tile_steps;
+                index = prod_end;
+                prod_end = index + ((g.M + sm.bm - 1) / sm.bm) * ((g.N + sm.bn - 1) / sm.bn) * slices;
+            }
+            if (!more) break;
+            active[nactive++] = prod_steps;
+            next_mine += 256;
+        }
+        if (nactive == 0) break;
+        const double by_intake = (double)nactive * stage_kb / kIntakeKBPerUs;
+        const double step_us = sm.lat_us > by_intake ? sm.lat_us : by_intake;
+        double adv = active[0];
+        for (int i = 1; i < nactive; ++i) adv = active[i] < adv ? active[i] : adv;
+        t += adv * step_us;
+        int keep = 0;
+        for (int i = 0; i < nactive; ++i) {
+            const double left = active[i] - adv;
+            if (left > 1e-9) active[keep++] = left;
+        }
+        nactive = keep;
+    }
+    return t;
+}
+
+// xfer: 16 or 4 for the bf16 transfer kernel (4-byte transfers run the three shapes of four wavefronts), 0 for
+// the generic kernel
+inline int pick_cfg(const GemmDesc* d, int count, int xfer)
+{
+    if (xfer && forced_tile_shape() >= 0) return forced_tile_shape();   // flop_bench.h
+    bool narrow = true;   // no product wider than 64 columns: wider tiles would be mostly empty
     for (int i = 0; i < count; ++i) narrow = narrow && d[i].N <= 64;
-    if (!transfer_kernel) {   // generic kernel: 128x128 when that still gives every compute unit work, else 64x64
+    if (!xfer) {
         const int64_t t128 = count_tiles(d, count, 128, 128);
         return (t128 >= 320 && !narrow) ? 0 : 2;
     }
-    static const int bm[3] = {128, 128, 64}, bn[3] = {128, 64, 64}, occupancy[3] = {2, 2, 3};
-    static const double step_us[3] = {0.82, 0.59, 0.43};
     int order[kMaxGroup];
     for (int i = 0; i < count; ++i) order[i] = i;
     for (int i = 1; i < count; ++i)
         for (int j = i; j > 0 && d[order[j]].K > d[order[j - 1]].K; --j) { int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t; }
+    // Where the fitted constants cannot be trusted (they come from launches of one round of tiles): k groups
+    // only pay on a long contraction; 96-wide tiles only where they waste no columns; with one 256x128 block per
+    // unit nothing hides a tile's first load and store, so that shape needs a single round or long tiles
+    int64_t min_steps = INT64_MAX, max_steps = 0;
+    bool n96 = true;
+    for (int i = 0; i < count; ++i) {
+        if (d[i].M <= 0 || d[i].N <= 0) continue;
+        const int64_t st = (d[i].K + 63) / 64;
+        min_steps = st < min_steps ? st : min_steps;
+        max_steps = st > max_steps ? st : max_steps;
+        n96 = n96 && d[i].N % 96 == 0;
+    }
+    const int64_t t256 = count_tiles(d, count, 256, 128);
     int best = 2;
     double best_t = 0.0;
-    for (int cfg = 2; cfg >= (narrow ? 1 : 0); --cfg) {
-        // slots of the chip as (time free, how many), earliest first; tiles go to the earliest slots
-        struct Bucket { double t; int64_t n; };
-        Bucket q[2 * kMaxGroup + 2];
-        int nq = 1;
-        q[0] = {0.0, (int64_t)256 * occupancy[cfg]};
-        double ingest_bytes = 0.0, makespan = 0.0;
-        for (int oi = 0; oi < count; ++oi) {
-            const GemmDesc& g = d[order[oi]];
-            if (g.M <= 0 || g.N <= 0) continue;
-            const int slices = (g.seg || g.ext) ? 1 : plan_ksplit(g.M, g.N, g.K);
-            const int64_t steps = (((g.K + 63) / 64) + slices - 1) / slices;
-            int64_t tiles = ((g.M + bm[cfg] - 1) / bm[cfg]) * ((g.N + bn[cfg] - 1) / bn[cfg]) * slices;
-            const double dur = (double)(steps > 0 ? steps : 1) * step_us[cfg];
-            ingest_bytes += (double)tiles * (double)steps * (double)((bm[cfg] + bn[cfg]) * 128);
-            while (tiles > 0) {
-                // all slots free at the earliest time take a tile each (whole rounds at once while they are alone)
-                Bucket b = q[0];
-                int64_t take = b.n < tiles ? b.n : tiles;
-                double finish = b.t + dur;
-                if (nq == 1 && tiles >= 2 * b.n) {   // only one bucket: skip whole rounds
-                    const int64_t rounds = tiles / b.n;
-                    take = b.n; finish = b.t + dur * (double)rounds;
-                    tiles -= b.n * (rounds - 1);
-                }
-                tiles -= take;
-                if (take == b.n) { for (int k = 1; k < nq; ++k) q[k - 1] = q[k]; --nq; }
-                else q[0].n -= take;
-                // insert (finish, take), merging equal times; the list stays short: one bucket per distinct time
-                int pos = nq;
-                while (pos > 0 && q[pos - 1].t > finish) --pos;
-                if (pos > 0 && q[pos - 1].t == finish) q[pos - 1].n += take;
-                else if (nq < (int)(sizeof(q) / sizeof(q[0]))) { for (int k = nq; k > pos; --k) q[k] = q[k - 1]; q[pos] = {finish, take}; ++nq; }
-                else q[nq - 1].n += take;   // cannot happen with <= kMaxGroup durations; keep the count right
-                if (finish > makespan) makespan = finish;
-            }
-        }
-        const double ingest_us = ingest_bytes / 20.0e6;
-        const double t = makespan > ingest_us ? makespan : ingest_us;
-        if (cfg == 2 || t <= best_t * 1.02) { best = cfg; best_t = t < best_t || cfg == 2 ? t : best_t; }
+    bool first = true;
+    for (const ShapeModel& sm : kShapeModels) {   // from small to large tiles: a larger one wins ties (fewer bytes moved)
+        if (narrow && sm.bn > 64) continue;
+        if (xfer == 4 && !(sm.cfg <= 2)) continue;
+        if (sm.groups > 1 && max_steps < 32) continue;
+        if (sm.bn == 96 && !n96) continue;
+        if (sm.bm == 256 && !(t256 <= 256 || min_steps >= 32)) continue;
+        const double t = model_launch_us(sm, d, order, count);
+        if (first || t <= best_t * 1.01) { best = sm.cfg; best_t = first || t < best_t ? t : best_t; first = false; }
     }
     return best;
 }
@@ -415,7 +450,6 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
                  bool* carried = nullptr)
 {
     const GemmDesc* d = d_in;
-    const int cfg = pick_cfg(d, count, dt == FLOP_BF16);
     if (fused_tile_rows) *fused_tile_rows = 0;
     if (dt == FLOP_BF16 && count == 1 && lowrank_fits(d[0])) return launch_lowrank(d[0], stream);
     if (dt == FLOP_BF16) {
@@ -426,6 +460,7 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
             const int w = d[i].b_kmajor == d[0].b_kmajor ? dma_width(d[i], &min_split[i]) : 0;
             xfer = w < xfer ? w : xfer;
         }
+        const int cfg = pick_cfg(d, count, xfer);
         // k slices per product: what pays on short tile lists, at least what the operand sizes force
         GemmDesc ds[kMaxGroup];
         size_t used = 0;
@@ -466,11 +501,11 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
         }
         for (int i = 0; i < count; ++i)
             if (d[i].gate_alpha) return FLOP_ERR_HIP;   // callers check gate_fusable() first
-        return cfg == 0 ? launch_generic<uint16_t, 128>(d, count, stream) : launch_generic<uint16_t, 64>(d, count, stream);
+        return pick_cfg(d, count, 0) == 0 ? launch_generic<uint16_t, 128>(d, count, stream) : launch_generic<uint16_t, 64>(d, count, stream);
     }
     for (int i = 0; i < count; ++i)
         if (d[i].gate_alpha) return FLOP_ERR_HIP;
-    return cfg == 0 ? launch_generic<float, 128>(d, count, stream) : launch_generic<float, 64>(d, count, stream);
+    return pick_cfg(d, count, 0) == 0 ? launch_generic<float, 128>(d, count, stream) : launch_generic<float, 64>(d, count, stream);
 }
 
 // bwd workspace layout: [dh: n x ldh elements][partial: ceil(n/32) x r floats][k-split scratch of one phase]
