@@ -130,12 +130,38 @@ int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, in
     return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
 }
 
+inline int64_t count_tiles(const GemmDesc* d, int count, int bm, int bn);
+
+template <typename T, int B, int G = 1, int KW = 1>
+int launch_generic_groups(const GemmDesc* d, int count, hipStream_t stream)
+{
+    static AttrOnce attr;
+    return launch_tiles<sizeof(T), B, B>(gemm_tile_kernel<T, B, B, G, KW>, gemm_lds_bytes<B, B, G, KW>(), &attr,
+                                         (sizeof(T) == 2 ? 1000 : 0) + B + 10000 * (G - 1), kGemmThreads * G, d, count, stream);
+}
+
+// Generic kernel.  A launch of 64x64 tiles that leaves half of the compute units without a tile while every tile
+// has at least 8 steps runs with four k groups per block (1024 threads): such a launch lasts as long as one tile's
+// chain of load latencies and its own arithmetic on one unit, which the groups overlap; with a quarter of the
+// units busy or fewer the tiles shrink to 32x32 as well, each step's k split over a group's wavefronts.
 template <typename T, int B>
 int launch_generic(const GemmDesc* d, int count, hipStream_t stream)
 {
-    static AttrOnce attr;
-    return launch_tiles<sizeof(T), B, B>(gemm_tile_kernel<T, B, B>, gemm_lds_bytes<B, B>(), &attr,
-                                         (sizeof(T) == 2 ? 1000 : 0) + B, kGemmThreads, d, count, stream);
+    if constexpr (B == 64) {
+        constexpr int BK = kStepBytes / (int)sizeof(T);
+        int64_t min_k = INT64_MAX;
+        bool fixed = true;
+        for (int i = 0; i < count; ++i) {
+            if (d[i].M <= 0 || d[i].N <= 0) continue;
+            min_k = d[i].K < min_k ? d[i].K : min_k;
+            fixed = fixed && !(d[i].seg || d[i].ext);
+        }
+        if (fixed && min_k != INT64_MAX && min_k >= 8 * BK) {
+            if (count_tiles(d, count, 64, 64) <= 64) return launch_generic_groups<T, 32, 4, 4>(d, count, stream);
+            if (count_tiles(d, count, 64, 64) <= 128) return launch_generic_groups<T, 64, 4>(d, count, stream);
+        }
+    }
+    return launch_generic_groups<T, B, 1>(d, count, stream);
 }
 
 // Block shapes of the bf16 transfer kernel (see TileShape): tile, stage buffers, wave grid, k groups.

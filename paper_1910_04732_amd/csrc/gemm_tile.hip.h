@@ -224,7 +224,9 @@ struct TileStager {
                 if constexpr (ES == 2) {
                     // 16-bit element j of vector q; NV of them are packed in k order
                     auto el = [&](int q) { return (v[q][j >> 1] >> (16 * (j & 1))) & 0xFFFFu; };
-                    if constexpr (NV == 2) {
+                    if constexpr (NV == 1) {
+                        *(uint16_t*)dst = (uint16_t)el(0);
+                    } else if constexpr (NV == 2) {
                         *(uint32_t*)dst = el(0) | (el(1) << 16);
                     } else if constexpr (NV == 4) {
                         *(u32x2*)dst = u32x2{el(0) | (el(1) << 16), el(2) | (el(3) << 16)};
@@ -234,7 +236,9 @@ struct TileStager {
                                              el(4) | (el(5) << 16), el(6) | (el(7) << 16)};
                     }
                 } else {
-                    if constexpr (NV == 2) {
+                    if constexpr (NV == 1) {
+                        *(uint32_t*)dst = v[0][j];
+                    } else if constexpr (NV == 2) {
                         *(u32x2*)dst = u32x2{v[0][j], v[1][j]};
                     } else if constexpr (NV == 4) {
                         *(u32x4*)dst = u32x4{v[0][j], v[1][j], v[2][j], v[3][j]};
@@ -249,12 +253,21 @@ struct TileStager {
     }
 };
 
-template <typename T, int BM, int BN>
-__global__ __launch_bounds__(kGemmThreads) void gemm_tile_kernel(const GemmGroup grp)
+// G > 1: the block is G groups of four wavefronts that take the k steps of the tile in turn (group g the steps
+// g, g + G, ...), each with its own pair of stage buffers; their sums are added through LDS in a fixed order before
+// the epilogue.  A product with fewer tiles than compute units then has G loads in flight per tile instead of
+// one: its time is set by the latency of a step's loads, not by arithmetic.
+// KW = 4: the four wavefronts of a group do not split the tile but the k of a step (each a quarter of it, on the
+// whole tile), which lets the tile be as small as one 32x32 matrix instruction: the products of a 256 x 512 layer
+// are then 128 tiles instead of 32, and a tile's arithmetic is spread over sixteen wavefronts.
+template <typename T, int BM, int BN, int G = 1, int KW = 1>
+__global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(const GemmGroup grp)
 {
     constexpr int ES = sizeof(T);
     constexpr int BK = kStepBytes / ES;
-    constexpr int WTM = BM / 2, WTN = BN / 2;   // 2 x 2 waves
+    static_assert(KW == 1 || KW == 4, "a step's k goes to one wavefront or to the group's four");
+    constexpr int WGRID = KW == 1 ? 2 : 1;      // 2 x 2 wavefronts over the tile, or every wavefront on all of it
+    constexpr int WTM = BM / WGRID, WTN = BN / WGRID;
     constexpr int TM = WTM / 32, TN = WTN / 32; // 32x32 MFMA tiles per wave
     static_assert(TM >= 1 && TN >= 1, "tile too small");
     constexpr int A_BYTES = BM * kLdsRow, B_BYTES = BN * kLdsRow;
@@ -267,10 +280,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_tile_kernel(const GemmGroup
     if (!(locate_tile<ES, BM, BN>(grp, pr, tile_m, tile_n))) return;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int tid = threadIdx.x;
+    const int group = (int)threadIdx.x / kGemmThreads;   // wave-uniform
+    const int tid = (int)threadIdx.x % kGemmThreads;     // thread inside its group
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = KW == 1 ? wave >> 1 : 0, wn = KW == 1 ? wave & 1 : 0;
     const int l32 = lane & 31, lhi = lane >> 5;
+    unsigned char* gmem = smem + group * 2 * (A_BYTES + B_BYTES);   // the group's two stage buffers
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -282,26 +297,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_tile_kernel(const GemmGroup
 
     TileStager<ES, BM> sa;
     TileStager<ES, BN> sb;
-    const int nk = (pr.K + BK - 1) / BK;
+    // every group makes the same number of passes (the barriers are the block's); a pass beyond K loads zeros
+    const int nk = ((pr.K + BK - 1) / BK + G - 1) / G;
 
-    sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, 0, pr.M, pr.K, tid);
-    sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, 0, pr.N, pr.K, tid);
-    sa.store(smem, pr.a_kmajor, tid);
-    sb.store(smem + A_BYTES, pr.b_kmajor, tid);
+    sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, group * BK, pr.M, pr.K, tid);
+    sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, group * BK, pr.N, pr.K, tid);
+    sa.store(gmem, pr.a_kmajor, tid);
+    sb.store(gmem + A_BYTES, pr.b_kmajor, tid);
     __syncthreads();
 
     for (int s = 0; s < nk; ++s) {
-        unsigned char* cur = smem + (s & 1) * (A_BYTES + B_BYTES);
-        unsigned char* nxt = smem + ((s + 1) & 1) * (A_BYTES + B_BYTES);
+        unsigned char* cur = gmem + (s & 1) * (A_BYTES + B_BYTES);
+        unsigned char* nxt = gmem + ((s + 1) & 1) * (A_BYTES + B_BYTES);
         const bool more = (s + 1 < nk);
         if (more) {
-            sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, (s + 1) * BK, pr.M, pr.K, tid);
-            sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, (s + 1) * BK, pr.N, pr.K, tid);
+            sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, ((s + 1) * G + group) * BK, pr.M, pr.K, tid);
+            sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, ((s + 1) * G + group) * BK, pr.N, pr.K, tid);
         }
         const unsigned char* la = cur + (wm * WTM + l32) * kLdsRow + lhi * 16;
         const unsigned char* lb = cur + A_BYTES + (wn * WTN + l32) * kLdsRow + lhi * 16;
 #pragma unroll
-        for (int c = 0; c < kStepBytes / 32; ++c) {
+        for (int cc = 0; cc < kStepBytes / 32 / KW; ++cc) {
+            const int c = KW == 1 ? cc : wave;   // 32-byte piece of the step's k
             u32x4 af[TM], bf[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) af[i] = *(const u32x4*)(la + i * 32 * kLdsRow + c * 32);
@@ -334,6 +351,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_tile_kernel(const GemmGroup
         __syncthreads();
     }
 
+    // ---- partial sums added in a fixed order (the loop ended with a barrier: the stage buffers are free).
+    // Contributors: the G groups, times the group's four wavefronts when they split k; the first one collects.
+    if constexpr (G > 1 || KW > 1) {
+        float* part = (float*)smem;
+        constexpr int OWNERS = KW == 1 ? kGemmThreads : 64;   // threads of a contributor, each with its own outputs
+        constexpr int PER = TM * TN * 16 * OWNERS;
+        constexpr int NCONTRIB = G * KW;
+        const int cid = KW == 1 ? group : group * KW + wave;
+        const int otid = KW == 1 ? tid : lane;
+        if (cid > 0) {
+            float* mine = part + (cid - 1) * PER + otid;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mine[((i * TN + j) * 16 + v) * OWNERS] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (cid > 0) return;
+#pragma unroll 1
+        for (int gg = 1; gg < NCONTRIB; ++gg) {   // not unrolled: 16 values in flight per thread are enough
+            const float* theirs = part + (gg - 1) * PER + otid;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] += theirs[((i * TN + j) * 16 + v) * OWNERS];
+        }
+    }
+
     // ---- epilogue --------------------------------------------------------
     // Accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and
     // rows 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
@@ -359,10 +408,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_tile_kernel(const GemmGroup
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int G = 1, int KW = 1>
 constexpr size_t gemm_lds_bytes()
 {
-    return 2 * (size_t)(BM + BN) * kLdsRow;
+    const size_t stages = (size_t)G * 2 * (size_t)(BM + BN) * kLdsRow;
+    const size_t partials = (size_t)(G * KW - 1) * BM * BN * sizeof(float);
+    return stages > partials ? stages : partials;
 }
 
 }  // namespace flop

@@ -137,6 +137,18 @@ def test_layer_rows_padded_to_16_bytes(shape):
     check_layer(synth.layer_inputs(700 + n + d, n, d, r, dout, "bf16"), align=8)
 
 
+@pytest.mark.parametrize("dtype,shape,pad", [("f32", (260, 300, 258, 270), 0), ("f32", (257, 1030, 264, 291), 1),
+                                             ("f32", (600, 300, 520, 260), 0), ("bf16", (520, 530, 515, 540), 3),
+                                             ("bf16", (200, 530, 515, 190), 3)],
+                         ids=lambda v: v if isinstance(v, str) else ("x".join(map(str, v)) if isinstance(v, tuple) else f"pad{v}"))
+def test_generic_kernel_k_groups(dtype, shape, pad):
+    """Few tiles and long contractions on the register-staged kernel (float32; bfloat16 with odd leading
+    dimensions): blocks of four k groups on 64x64 tiles (65 to 128 tiles) and on 32x32 tiles whose k steps are
+    split over the wavefronts (up to 64 tiles of 64x64), with a ragged last round of the groups."""
+    n, d, r, dout = shape
+    check_layer(synth.layer_inputs(5200 + n + d, n, d, r, dout, dtype), pad=pad)
+
+
 @pytest.mark.parametrize("beta", [1.0, 0.5])
 def test_layer_other_temperatures(beta):
     c = synth.layer_inputs(55, 70, 48, 64, 40, "f32")
