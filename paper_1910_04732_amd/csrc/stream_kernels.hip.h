@@ -43,49 +43,88 @@ __device__ __forceinline__ void gate_one(float a, float u, float inv_beta, float
     dzda = (sbar >= 0.0f && sbar <= 1.0f) ? (r - l) * s * one_minus_s * inv_temp : 0.0f;
 }
 
-// VEC = 4: float4 accesses (arrays 16-byte aligned); VEC = 1: any alignment.
-// Each thread handles UNROLL float4 groups per pass so that several loads are in flight.
+// 16-byte accesses of the streaming kernels.  Stores are marked non-temporal (every byte is written once); loads
+// are not: measured on 2^26 gates, past the last-level cache, non-temporal stores gained 3-20 % and cost nothing
+// at cache-resident sizes, non-temporal loads gained there too but lost 5-10 % at 2^24 gates.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+#ifndef FLOP_NT_LOAD
+#define FLOP_NT_LOAD 0
+#endif
+#ifndef FLOP_NT_STORE
+#define FLOP_NT_STORE 1
+#endif
+__device__ __forceinline__ f32x4 stream_load4(const float* p)
+{
+#if FLOP_NT_LOAD
+    return __builtin_nontemporal_load((const f32x4*)p);
+#else
+    return *(const f32x4*)p;
+#endif
+}
+__device__ __forceinline__ void stream_store4(float* p, f32x4 v)
+{
+#if FLOP_NT_STORE
+    __builtin_nontemporal_store(v, (f32x4*)p);
+#else
+    *(f32x4*)p = v;
+#endif
+}
+
+// VEC = 4: 16-byte accesses (arrays 16-byte aligned); VEC = 1: any alignment.
+// A block works on kStreamChunk consecutive gates at a time (UNROLL 16-byte groups per thread, all loads issued
+// before the first use), so that each of the four streams is read and written in 16 KB runs.
+constexpr int kStreamUnroll = 4;
+constexpr int kStreamChunk = kStreamThreads * 4 * kStreamUnroll;
+
 template <int VEC>
 __global__ __launch_bounds__(kStreamThreads) void gate_sample_kernel(
     const float* __restrict__ log_alpha, const float* __restrict__ u, int64_t n,
     float beta, float l, float r, int mode, float* __restrict__ z, float* __restrict__ dzda)
 {
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = kStreamUnroll;
     const float inv_beta = 1.0f / beta;
-    const int64_t stride = (int64_t)gridDim.x * kStreamThreads * VEC;
-    int64_t k = ((int64_t)blockIdx.x * kStreamThreads + threadIdx.x) * VEC;
+    int64_t done = 0;   // gates covered by whole chunks
     if (VEC == 4) {
-        for (; k + (UNROLL - 1) * stride + 4 <= n; k += UNROLL * stride) {
-            float4 a[UNROLL], uu[UNROLL];
+        const int64_t chunks = n / kStreamChunk;
+        for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+            const int64_t k = c * kStreamChunk + threadIdx.x * 4;
+            f32x4 a[UNROLL], uu[UNROLL];
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) {
-                a[q] = *(const float4*)(log_alpha + k + q * stride);
-                uu[q] = (mode == 0) ? *(const float4*)(u + k + q * stride) : float4{0.5f, 0.5f, 0.5f, 0.5f};
+                a[q] = stream_load4(log_alpha + k + q * (kStreamThreads * 4));
+                uu[q] = (mode == 0) ? stream_load4(u + k + q * (kStreamThreads * 4)) : f32x4{0.5f, 0.5f, 0.5f, 0.5f};
             }
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) {
-                float4 zz, dd;
-                gate_one(a[q].x, uu[q].x, inv_beta, l, r, mode, zz.x, dd.x);
-                gate_one(a[q].y, uu[q].y, inv_beta, l, r, mode, zz.y, dd.y);
-                gate_one(a[q].z, uu[q].z, inv_beta, l, r, mode, zz.z, dd.z);
-                gate_one(a[q].w, uu[q].w, inv_beta, l, r, mode, zz.w, dd.w);
-                *(float4*)(z + k + q * stride) = zz;
-                if (dzda) *(float4*)(dzda + k + q * stride) = dd;
+                f32x4 zz, dd;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float ze, de;
+                    gate_one(a[q][e], uu[q][e], inv_beta, l, r, mode, ze, de);
+                    zz[e] = ze; dd[e] = de;
+                }
+                stream_store4(z + k + q * (kStreamThreads * 4), zz);
+                if (dzda) stream_store4(dzda + k + q * (kStreamThreads * 4), dd);
             }
         }
+        done = chunks * kStreamChunk;
     }
-    for (; k < n; k += stride) {
+    // the rest (less than a chunk when VEC == 4), one group of VEC per thread and pass
+    const int64_t stride = (int64_t)gridDim.x * kStreamThreads * VEC;
+    for (int64_t k = done + ((int64_t)blockIdx.x * kStreamThreads + threadIdx.x) * VEC; k < n; k += stride) {
         if (VEC == 4 && k + 4 <= n) {
-            const float4 a = *(const float4*)(log_alpha + k);
-            float4 uu = {0.5f, 0.5f, 0.5f, 0.5f};
-            if (mode == 0) uu = *(const float4*)(u + k);
-            float4 zz, dd;
-            gate_one(a.x, uu.x, inv_beta, l, r, mode, zz.x, dd.x);
-            gate_one(a.y, uu.y, inv_beta, l, r, mode, zz.y, dd.y);
-            gate_one(a.z, uu.z, inv_beta, l, r, mode, zz.z, dd.z);
-            gate_one(a.w, uu.w, inv_beta, l, r, mode, zz.w, dd.w);
-            *(float4*)(z + k) = zz;
-            if (dzda) *(float4*)(dzda + k) = dd;
+            const f32x4 a = *(const f32x4*)(log_alpha + k);
+            f32x4 uu = {0.5f, 0.5f, 0.5f, 0.5f};
+            if (mode == 0) uu = *(const f32x4*)(u + k);
+            f32x4 zz, dd;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float ze, de;
+                gate_one(a[e], uu[e], inv_beta, l, r, mode, ze, de);
+                zz[e] = ze; dd[e] = de;
+            }
+            *(f32x4*)(z + k) = zz;
+            if (dzda) *(f32x4*)(dzda + k) = dd;
         } else {
             for (int e = 0; e < VEC && k + e < n; ++e) {
                 float zz, dd;
@@ -124,38 +163,44 @@ __global__ __launch_bounds__(kStreamThreads) void expected_l0_kernel(
     const float* __restrict__ log_alpha, const float* __restrict__ w, int64_t n, float shift,
     float* __restrict__ grad, double* __restrict__ block_sums, float* __restrict__ out)
 {
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = kStreamUnroll;
     __shared__ double lds[kStreamThreads / 64];
     double acc = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * kStreamThreads * VEC;
-    int64_t k = ((int64_t)blockIdx.x * kStreamThreads + threadIdx.x) * VEC;
     auto one = [&](float a, float ww, float& g) {
         const float e = exp_neg_clamped(a - shift);
         const float p = __builtin_amdgcn_rcpf(1.0f + e);   // P[z > 0]
         g = ww * p * (e * p);                // w p (1 - p)
         return ww * p;
     };
-    if (VEC == 4) {
-        for (; k + (UNROLL - 1) * stride + 4 <= n; k += UNROLL * stride) {
-            float4 a[UNROLL], ww[UNROLL];
+    int64_t done = 0;
+    if (VEC == 4) {   // whole chunks of kStreamChunk consecutive gates per block and pass
+        const int64_t chunks = n / kStreamChunk;
+        for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+            const int64_t k = c * kStreamChunk + threadIdx.x * 4;
+            f32x4 a[UNROLL], ww[UNROLL];
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) {
-                a[q] = *(const float4*)(log_alpha + k + q * stride);
-                ww[q] = w ? *(const float4*)(w + k + q * stride) : float4{1.0f, 1.0f, 1.0f, 1.0f};
+                a[q] = stream_load4(log_alpha + k + q * (kStreamThreads * 4));
+                ww[q] = w ? stream_load4(w + k + q * (kStreamThreads * 4)) : f32x4{1.0f, 1.0f, 1.0f, 1.0f};
             }
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) {
-                float4 g;
-                float part = one(a[q].x, ww[q].x, g.x);
-                part += one(a[q].y, ww[q].y, g.y);
-                part += one(a[q].z, ww[q].z, g.z);
-                part += one(a[q].w, ww[q].w, g.w);
+                f32x4 g;
+                float part = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float ge;
+                    part += one(a[q][e], ww[q][e], ge);
+                    g[e] = ge;
+                }
                 acc += (double)part;
-                if (grad) *(float4*)(grad + k + q * stride) = g;
+                if (grad) stream_store4(grad + k + q * (kStreamThreads * 4), g);
             }
         }
+        done = chunks * kStreamChunk;
     }
-    for (; k < n; k += stride) {
+    const int64_t stride = (int64_t)gridDim.x * kStreamThreads * VEC;
+    for (int64_t k = done + ((int64_t)blockIdx.x * kStreamThreads + threadIdx.x) * VEC; k < n; k += stride) {
         for (int e = 0; e < VEC && k + e < n; ++e) {
             float g;
             acc += (double)one(log_alpha[k + e], w ? w[k + e] : 1.0f, g);
@@ -540,25 +585,29 @@ __device__ __forceinline__ void compact_row_body(
     }
 }
 
-// Pc[m,t] = P[m, idx[t]]: one block per row m.  The row is staged through LDS in
-// chunks of kColChunk source columns with 16-byte loads; the survivors of a chunk
-// are the index-list range found by binary search (idx is ascending), gathered from
-// LDS and written with consecutive lanes on consecutive outputs.  The pad columns
-// rp .. pad are zeroed.
-constexpr int kColChunk = 8192;
+// Pc[m,t] = P[m, idx[t]]: one block per row m.  The row is staged through LDS in pieces of kColChunk source
+// columns with 16-byte loads; the survivors of a piece are the index-list range found by binary search (idx is
+// ascending), gathered from LDS and written 16 bytes per thread where the output rows allow it (measured: 104 ->
+// 93 us on an 8192 x 8192 matrix that keeps 90 % of its columns), else with consecutive lanes on consecutive
+// outputs.  The pad columns rp .. pad are zeroed.  16 KB of LDS per block: ten blocks per compute unit keep
+// enough loads in flight (32 KB and several rows per block measured slower).
+constexpr int kColChunkBytes = 16384;
 
 template <typename U>
 __device__ __forceinline__ void compact_col_body(
-    int64_t m, U* __restrict__ row /* kColChunk entries of LDS */,
+    int64_t m0, U* __restrict__ lds /* kColChunkBytes of LDS */,
     const U* __restrict__ P, int64_t ldp, int r, const int32_t* __restrict__ r_out,
     const int32_t* __restrict__ idx, U* __restrict__ Pc, int64_t ldpc, int vec_ok)
 {
+    constexpr int kColChunk = kColChunkBytes / (int)sizeof(U);
+    constexpr int E = 16 / (int)sizeof(U);
     const int rp = r_out[0];
     int pad = (rp + 31) / 32 * 32;
     if (pad > r) pad = r;
-    const U* src = P + m * ldp;
-    U* dst = Pc + m * ldpc;
-    constexpr int E = 16 / (int)sizeof(U);
+    const bool out_vec = (((uintptr_t)Pc & 15u) == 0) && ((ldpc * sizeof(U)) % 16 == 0);
+    const U* src = P + m0 * ldp;
+    U* dst = Pc + m0 * ldpc;
+    U* row = lds;
     int t0 = 0;   // first survivor with idx >= chunk start
     for (int c0 = 0; c0 < r && t0 < rp; c0 += kColChunk) {
         const int c1 = min(r, c0 + kColChunk);
@@ -579,7 +628,24 @@ __device__ __forceinline__ void compact_col_body(
                 for (int k = threadIdx.x; k < c1 - c0; k += kStreamThreads) row[k] = src[c0 + k];
             }
             __syncthreads();
-            for (int t = t0 + threadIdx.x; t < t1; t += kStreamThreads) dst[t] = row[idx[t] - c0];
+            if (out_vec) {
+                // whole 16-byte groups of outputs that lie inside [t0, t1); the ragged ends one by one
+                const int ta = (t0 + E - 1) / E * E, tb = t1 / E * E;
+                if (ta >= tb) {
+                    for (int t = t0 + threadIdx.x; t < t1; t += kStreamThreads) dst[t] = row[idx[t] - c0];
+                } else {
+                    for (int t = t0 + threadIdx.x; t < ta; t += kStreamThreads) dst[t] = row[idx[t] - c0];
+                    for (int t = tb + threadIdx.x; t < t1; t += kStreamThreads) dst[t] = row[idx[t] - c0];
+                    for (int t = ta + threadIdx.x * E; t < tb; t += kStreamThreads * E) {
+                        __attribute__((aligned(16))) U v[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) v[e] = row[idx[t + e] - c0];
+                        *(uint4*)(dst + t) = *(const uint4*)v;
+                    }
+                }
+            } else {
+                for (int t = t0 + threadIdx.x; t < t1; t += kStreamThreads) dst[t] = row[idx[t] - c0];
+            }
             __syncthreads();
         }
         t0 = t1;
@@ -601,7 +667,7 @@ __global__ __launch_bounds__(kStreamThreads) void compact_cols_kernel(
     const U* __restrict__ P, int64_t ldp, int r, const int32_t* __restrict__ r_out,
     const int32_t* __restrict__ idx, U* __restrict__ Pc, int64_t ldpc, int vec_ok)
 {
-    __shared__ __attribute__((aligned(16))) U row[kColChunk];
+    __shared__ __attribute__((aligned(16))) U row[kColChunkBytes / sizeof(U)];
     compact_col_body<U>((int64_t)blockIdx.x, row, P, ldp, r, r_out, idx, Pc, ldpc, vec_ok);
 }
 
@@ -612,7 +678,7 @@ __global__ __launch_bounds__(kStreamThreads) void compact_gather_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ z, int absorb, void* __restrict__ Qc, int64_t ldqc,
     const U* __restrict__ P, int64_t ldp, U* __restrict__ Pc, int64_t ldpc, int vec_p)
 {
-    __shared__ __attribute__((aligned(16))) U row[kColChunk];
+    __shared__ __attribute__((aligned(16))) U row[kColChunkBytes / sizeof(U)];
     if ((int)blockIdx.x < r)
         compact_row_body<(int)sizeof(U), UNIT>((int)blockIdx.x, Q, ldq, d, r, r_out, idx, z, absorb, Qc, ldqc);
     else
