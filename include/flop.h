@@ -424,6 +424,36 @@ int flop_expand_grads(flop_dtype dt, int64_t d, int64_t r, int64_t dout,
                       void* dQ, int64_t lddq, void* dP, int64_t lddp, float* dlog_alpha, void* stream);
 
 /*
+ * Train-time active ranks without compacted copies of the factors (Section 4.3, last
+ * paragraph; Section 4.1: a closed component adds nothing to y nor to any gradient).
+ * The contractions read the open components straight out of the full-size factors
+ * through the ascending index list idx[0 .. r_active[0]) that flop_active_prepare
+ * (with Qc = Pc = NULL: one launch) or flop_compact wrote, and write the gradients of
+ * those components straight into the full-size gradients.  For both factors to be
+ * gathered by rows, P is held transposed:
+ *   Pt[r, dout] ld ldpt: row k is the column p_k of P;  dPt[r, dout] likewise.
+ *   zc[r], dzda_c[r]: gates and dz/dalpha of the open components in idx order
+ *   g_active[n, r_active] ld ldg (ldg >= r): the saved activation (x Q[idx]^T) .* zc
+ * Forward: y = g_active Pt[idx].  Backward: dx; rows idx of dQ and dPt; dlog_alpha[idx];
+ * every other row of dQ and dPt and (unless accumulate != 0) entry of dlog_alpha is set
+ * to exact zero, their true value.  dx, dQ, dPt, dlog_alpha are nullable.
+ * workspace of the backward: >= flop_workspace_bytes(FLOP_OP_BWD, dt, n, d, r, dout).
+ * Same results as flop_fwd / flop_bwd on (Q, P = Pt^T, z) up to summation order.
+ */
+int flop_fwd_active_indexed(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                            const void* x, int64_t ldx, const void* Q, int64_t ldq, const void* Pt, int64_t ldpt,
+                            const float* zc, const int32_t* idx, const int32_t* r_active,
+                            void* g_active, int64_t ldg, void* y, int64_t ldy, void* stream);
+int flop_bwd_active_indexed(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                            const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                            const void* Q, int64_t ldq, const void* Pt, int64_t ldpt,
+                            const float* zc, const float* dzda_c, const int32_t* idx, const int32_t* r_active,
+                            const void* g_active, int64_t ldg,
+                            void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dPt, int64_t lddpt,
+                            float* dlog_alpha, int accumulate,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Deterministic mask for inference as Section 4.4 states it: each gate is scored
  * by its term of Eq.(3), p_k = sigmoid(log_alpha_k - beta * log(-l / r)), the
  * `keep` best are kept and the rest clipped to zero, so that the number of open

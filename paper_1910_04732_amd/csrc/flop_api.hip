@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <initializer_list>
 #include <mutex>
 #include <vector>
 
@@ -29,6 +30,12 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool valid_dtype(int dt) { return dt == FLOP_F32 || dt == FLOP_BF16; }
 inline bool valid_hc(flop_hc hc) { return hc.l < 0.0f && hc.r > 1.0f && hc.beta > 0.0f; }
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
+constexpr int64_t kMaxLd = (int64_t)1 << 32;   // leading dimensions beyond this are taken for a caller's mistake
+inline bool ld_too_large(std::initializer_list<int64_t> lds)
+{
+    for (int64_t v : lds) if (v > kMaxLd) return true;
+    return false;
+}
 
 // ------------------------------------------------------------------------
 // Contraction launcher
@@ -51,6 +58,8 @@ struct GemmDesc {
     // gate computed in the epilogue instead of col_scale (see GemmProblem); only for products that
     // gate_fusable() accepts
     const float* gate_alpha; const float* gate_u; float gate_beta, gate_l, gate_r;
+    // B gathered by an index list (see GemmProblem): rows of the b_map_rows-row matrix at B
+    const int32_t* b_map; int64_t b_map_rows;
 };
 
 // Kernels that need more dynamic LDS than the default limit get the attribute once per device (a function's
@@ -68,17 +77,22 @@ struct AttrOnce {
 
 // One launch of a tile kernel over up to kMaxGroup products.  Products are ordered
 // by decreasing k extent so that the longest tiles are dispatched first.
+// lds_extra: what a launch with a B gathered along k adds for its table (only such launches ask for it)
 template <int ES, int BM, int BN>
 int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, int kernel_id, int threads,
                  const GemmDesc* d_in, int count, hipStream_t stream, const BoundaryRider* rider = nullptr,
-                 bool* carried = nullptr)
+                 bool* carried = nullptr, size_t lds_extra = 0)
 {
     int dev = 0;
     if (attr->needed(&dev)) {
-        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(lds + lds_extra)) != hipSuccess)
             return FLOP_ERR_HIP;
         attr->done(dev);
     }
+    bool k_gather = false;
+    for (int i = 0; i < count; ++i) k_gather = k_gather || (d_in[i].b_map && !d_in[i].b_kmajor);
+    if (k_gather) lds += lds_extra;
+    if (lds > 160 * 1024) return FLOP_ERR_SHAPE;   // beyond a compute unit's LDS (no shape of this library reaches it)
     GemmDesc d[kMaxGroup];
     for (int i = 0; i < count; ++i) d[i] = d_in[i];
     for (int i = 1; i < count; ++i)
@@ -99,6 +113,7 @@ int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, in
         p.dot = d[i].dot; p.lddot = d[i].lddot; p.dot_partial = d[i].dot_partial; p.dot_ld = d[i].N;
         p.ext = d[i].ext; p.ext_dim = d[i].ext_dim;
         p.ksplit = d[i].ksplit; p.split_out = d[i].split_out;
+        p.b_map = d[i].b_map; p.b_map_rows = (int)d[i].b_map_rows;
         p.lda = d[i].lda; p.ldb = d[i].ldb; p.ldc = d[i].ldc;
         p.M = (int)d[i].M; p.N = (int)d[i].N; p.K = (int)d[i].K;
         p.tiles_m = (int)((d[i].M + BM - 1) / BM);
@@ -192,7 +207,7 @@ int launch_dma(const GemmDesc* d, int count, hipStream_t stream, const BoundaryR
     static AttrOnce attr;
     return launch_tiles<2, SH::BM, SH::BN>(gemm_bf16_dma_kernel<SH, BKM, XFER>, gemm_dma_lds_bytes<SH>(), &attr,
                                            1100 + (SH::BM + SH::BN) / 2 + 10000 * (SH::G - 1), SH::THREADS, d, count,
-                                           stream, rider, carried);
+                                           stream, rider, carried, (!BKM && XFER == 16) ? (size_t)kKtabBytes : 0);
 }
 
 // The DMA kernel describes each operand with a buffer descriptor whose range is below 2 GiB.  For a
@@ -234,10 +249,15 @@ int dma_width(const GemmDesc& g, int* min_split)
         if (sl > need) need = sl;
         return sl > 0;
     };
-    if (!fits(g.a_kmajor, g.lda, g.M) || !fits(g.b_kmajor, g.ldb, g.N)) return 0;
+    if (!fits(g.a_kmajor, g.lda, g.M)) return 0;
+    if (g.b_map) {   // a gathered B is described whole, and its k rows by 16-bit entries of a table of kKtabMaxK
+        if (((g.b_map_rows - 1) * g.ldb + round_up(g.b_kmajor ? g.K : g.N, 8)) * 2 >= kDescLimit) return 0;
+        if (!g.b_kmajor && (g.K > kKtabMaxK || g.b_map_rows >= (int64_t)kKtabNone)) return 0;
+    } else if (!fits(g.b_kmajor, g.ldb, g.N)) return 0;
     *min_split = need;
     const int wa = align(g.A, g.lda), wb = align(g.B, g.ldb);
-    return wa < wb ? wa : wb;
+    const int w = wa < wb ? wa : wb;
+    return (g.b_map && w != 16) ? 0 : w;   // gathered operands: 16-byte transfers or the generic kernel
 }
 
 inline int64_t count_tiles(const GemmDesc* d, int count, int bm, int bn)
@@ -296,7 +316,7 @@ inline double model_launch_us(const ShapeModel& sm, const GemmDesc* d, const int
                 if (oi >= count) { more = false; break; }
                 const GemmDesc& g = d[order[oi++]];
                 if (g.M <= 0 || g.N <= 0) continue;
-                const int slices = (g.seg || g.ext) ? 1 : plan_ksplit(g.M, g.N, g.K);
+                const int slices = (g.seg || g.ext || g.b_map) ? 1 : plan_ksplit(g.M, g.N, g.K);
                 int64_t steps = (((g.K + 63) / 64) + slices - 1) / slices;
                 steps = (steps + sm.groups - 1) / sm.groups;
                 prod_steps = (double)(steps > 0 ? steps : 1) + tile_steps;
@@ -493,7 +513,7 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
         bool any_split = false, dot_lost = false;
         for (int i = 0; i < count && xfer; ++i) {
             ds[i] = d[i];
-            const bool fixed_extents = !(ds[i].seg || ds[i].ext);
+            const bool fixed_extents = !(ds[i].seg || ds[i].ext || ds[i].b_map);
             int sl = fixed_extents ? plan_ksplit(ds[i].M, ds[i].N, ds[i].K) : 1;
             if (sl > 1 && !(split_ws && used + split_bytes_for(sl, ds[i].M, ds[i].N) <= split_bytes)) sl = 1;
             if (sl < min_split[i]) {
@@ -650,7 +670,8 @@ int validate_embed(flop_dtype dt, int64_t n_tokens, int32_t n_clusters, const fl
 // dlog_alpha_k = (sum_i dh_ik g_ik) / z_k^2 * dzda_k: chunked column reduction, then the finish kernel.
 int launch_gate_grad(flop_dtype dt, int64_t n, int64_t r, const void* dh, int64_t ldh, const void* g, int64_t ldg,
                      const float* z, const float* dzda, float* dlog_alpha, int accumulate, float* partial,
-                     hipStream_t st, const int32_t* r_active = nullptr, flop_gate_grad_pending* pending = nullptr)
+                     hipStream_t st, const int32_t* r_active = nullptr, flop_gate_grad_pending* pending = nullptr,
+                     const int32_t* out_map = nullptr)
 {
     // 32-row chunks fill the chip for small n; long inputs use 128-row chunks (more loads in flight per lane)
     const int chunk_rows = (n >= 16384) ? 128 : kColsumChunkRows;
@@ -674,7 +695,7 @@ int launch_gate_grad(flop_dtype dt, int64_t n, int64_t r, const void* dh, int64_
     }
     hipLaunchKernelGGL(dalpha_finish_kernel, dim3((unsigned)((r + 31) / 32)), dim3(kStreamThreads), 0, st,
                        (const float*)partial, chunks, r, z, dzda, dlog_alpha, accumulate, (const int32_t*)nullptr, chunk_rows,
-                       r_active);
+                       r_active, out_map);
     return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
 }
 
@@ -691,6 +712,7 @@ int fwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
     if (n == 0) return FLOP_OK;
     if (!x || !Q || !P || !z || !g_saved || !y) return FLOP_ERR_NULL;
     if (ldx < d || ldq < d || ldp < r || ldg < r || ldy < dout) return FLOP_ERR_STRIDE;
+    if (ld_too_large({ldx, ldq, ldp, ldg, ldy})) return FLOP_ERR_STRIDE;
     if (workspace && ((uintptr_t)workspace & 255u) != 0) return FLOP_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     if (!workspace) workspace_bytes = 0;   // the workspace is optional: it only enables k-split launches
@@ -788,6 +810,7 @@ int bwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
     if (pending && !dlog_alpha) return FLOP_ERR_NULL;
     if (lddy < dout || ldx < d || ldq < d || ldp < r || ldg < r) return FLOP_ERR_STRIDE;
     if ((dx && lddx < d) || (dQ && lddq < d) || (dP && lddp < r)) return FLOP_ERR_STRIDE;
+    if (ld_too_large({lddy, ldx, ldq, ldp, ldg, lddx, lddq, lddp})) return FLOP_ERR_STRIDE;
     if (!workspace || workspace_bytes < flop_workspace_bytes(FLOP_OP_BWD, dt, n, d, r, dout))
         return FLOP_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255u) != 0) return FLOP_ERR_ALIGN;
@@ -868,7 +891,7 @@ int bwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
         } else {
             hipLaunchKernelGGL(dalpha_finish_kernel, dim3((unsigned)((r + 31) / 32)), dim3(kStreamThreads), 0, st,
                                (const float*)partial, chunks, r, z, dzda, dlog_alpha,
-                               accumulate, (const int32_t*)nullptr, fused_rows, r_active);
+                               accumulate, (const int32_t*)nullptr, fused_rows, r_active, (const int32_t*)nullptr);
             if (hipGetLastError() != hipSuccess) return FLOP_ERR_HIP;
         }
     } else if (dlog_alpha) {
@@ -1014,6 +1037,7 @@ int flop_fwd_sampling(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t do
     if (n < 0 || d <= 0 || dout <= 0 || n > kMaxDim || d > kMaxDim || r > kMaxDim || dout > kMaxDim) return FLOP_ERR_SHAPE;
     if (n > 0 && (!x || !Q || !P || !g_saved || !y)) return FLOP_ERR_NULL;
     if (ldx < d || ldq < d || ldp < r || ldg < r || ldy < dout) return FLOP_ERR_STRIDE;
+    if (ld_too_large({ldx, ldq, ldp, ldg, ldy})) return FLOP_ERR_STRIDE;
     if (workspace && ((uintptr_t)workspace & 255u) != 0) return FLOP_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     GemmDesc g1 = {x, ldx, true, Q, ldq, true, g_saved, ldg, n, r, d, nullptr};
@@ -1128,6 +1152,115 @@ int flop_bwd_active(flop_dtype dt, int64_t n, int64_t d, int64_t r_cap, int64_t 
     if (!r_active) return FLOP_ERR_NULL;
     return bwd_impl(dt, n, d, r_cap, dout, dy, lddy, x, ldx, Qc, ldqc, Pc, ldpc, zc, dzda_c, r_active, g_saved, ldg,
                     dx, lddx, dQc, lddqc, dPc, lddpc, dlog_alpha_c, accumulate, workspace, workspace_bytes, stream);
+}
+
+// ---- active ranks read in place (flop.h: flop_fwd_active_indexed / flop_bwd_active_indexed) -------------------
+int flop_fwd_active_indexed(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                            const void* x, int64_t ldx, const void* Q, int64_t ldq, const void* Pt, int64_t ldpt,
+                            const float* zc, const int32_t* idx, const int32_t* r_active,
+                            void* g_active, int64_t ldg, void* y, int64_t ldy, void* stream)
+{
+    if (!valid_dtype(dt)) return FLOP_ERR_DTYPE;
+    if (n < 0 || d <= 0 || r <= 0 || dout <= 0) return FLOP_ERR_SHAPE;
+    if (n > kMaxDim || d > kMaxDim || r > kMaxDim || dout > kMaxDim) return FLOP_ERR_SHAPE;
+    if (n == 0) return FLOP_OK;
+    if (!x || !Q || !Pt || !zc || !idx || !r_active || !g_active || !y) return FLOP_ERR_NULL;
+    if (ldx < d || ldq < d || ldpt < dout || ldg < r || ldy < dout) return FLOP_ERR_STRIDE;
+    if (ld_too_large({ldx, ldq, ldpt, ldg, ldy})) return FLOP_ERR_STRIDE;
+    hipStream_t st = (hipStream_t)stream;
+    // g = (x Q[idx]^T) .* zc: the rows of Q are gathered
+    GemmDesc g1 = {x, ldx, true, Q, ldq, true, g_active, ldg, n, r, d, zc};
+    g1.ext = r_active; g1.ext_dim = 3; g1.b_map = idx; g1.b_map_rows = r;
+    int rc = launch_group(dt, &g1, 1, st);
+    if (rc != FLOP_OK) return rc;
+    // y = g Pt[idx]: the contraction runs down the gathered rows of Pt
+    GemmDesc g2 = {g_active, ldg, true, Pt, ldpt, false, y, ldy, n, dout, r, nullptr};
+    g2.ext = r_active; g2.ext_dim = 2; g2.b_map = idx; g2.b_map_rows = r;
+    return launch_group(dt, &g2, 1, st);
+}
+
+int flop_bwd_active_indexed(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                            const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                            const void* Q, int64_t ldq, const void* Pt, int64_t ldpt,
+                            const float* zc, const float* dzda_c, const int32_t* idx, const int32_t* r_active,
+                            const void* g_active, int64_t ldg,
+                            void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dPt, int64_t lddpt,
+                            float* dlog_alpha, int accumulate,
+                            void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!valid_dtype(dt)) return FLOP_ERR_DTYPE;
+    if (n < 0 || d <= 0 || r <= 0 || dout <= 0) return FLOP_ERR_SHAPE;
+    if (n > kMaxDim || d > kMaxDim || r > kMaxDim || dout > kMaxDim) return FLOP_ERR_SHAPE;
+    if (!Q || !Pt || !zc || !idx || !r_active) return FLOP_ERR_NULL;
+    if (n > 0 && (!dy || !x || !g_active)) return FLOP_ERR_NULL;
+    if (dlog_alpha && !dzda_c) return FLOP_ERR_NULL;
+    if (lddy < dout || ldx < d || ldq < d || ldpt < dout || ldg < r) return FLOP_ERR_STRIDE;
+    if ((dx && lddx < d) || (dQ && lddq < d) || (dPt && lddpt < dout)) return FLOP_ERR_STRIDE;
+    if (ld_too_large({lddy, ldx, ldq, ldpt, ldg, lddx, lddq, lddpt})) return FLOP_ERR_STRIDE;
+    if (!workspace || workspace_bytes < flop_workspace_bytes(FLOP_OP_BWD, dt, n, d, r, dout)) return FLOP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return FLOP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const int es = (int)elem_size(dt);
+
+    // closed components: exact zeros in their rows of dQ and dPt and (unless added to) entries of dlog_alpha; the
+    // rows of the open ones are written by the products below
+    if (dQ || dPt || (dlog_alpha && !accumulate)) {
+        hipLaunchKernelGGL(zero_closed_rows_kernel, dim3((unsigned)r), dim3(kStreamThreads), 0, st, idx, r_active, (int)r,
+                           dQ, lddq, (int)d, dPt, lddpt, (int)dout, es, (dlog_alpha && !accumulate) ? dlog_alpha : (float*)nullptr);
+        if (hipGetLastError() != hipSuccess) return FLOP_ERR_HIP;
+    }
+    if (n == 0) return FLOP_OK;
+
+    void* dh = workspace;
+    const int64_t ldh = bwd_ldh(r, dt);
+    float* partial = (float*)((char*)workspace + bwd_dh_bytes(n, r, dt));
+    const bool need_dh = dx || dQ || dlog_alpha;
+    int rc;
+    int fused_rows = 0;
+    // dh = (dy Pt[idx]^T) .* zc (rows of Pt gathered), with the column sums of dh .* g where the kernel can
+    if (need_dh) {
+        GemmDesc p1 = {dy, lddy, true, Pt, ldpt, true, dh, ldh, n, r, dout, zc};
+        p1.ext = r_active; p1.ext_dim = 3; p1.b_map = idx; p1.b_map_rows = r;
+        if (dlog_alpha && dt == FLOP_BF16 && ((uintptr_t)g_active & 3u) == 0 && ldg % 2 == 0) {
+            p1.dot = g_active; p1.lddot = ldg; p1.dot_partial = partial;
+        }
+        rc = launch_group(dt, &p1, 1, st, &fused_rows);
+        if (rc != FLOP_OK) return rc;
+        if (!p1.dot_partial) fused_rows = 0;
+    }
+    // dPt[idx] = g^T dy, dQ[idx] = dh^T x (rows scattered by the index list), dx = dh Q[idx] (contraction down
+    // the gathered rows of Q): one launch
+    GemmDesc p2[3];
+    int c2 = 0;
+    if (dPt) {
+        p2[c2] = {g_active, ldg, false, dy, lddy, false, dPt, lddpt, r, dout, n, nullptr};
+        p2[c2].ext = r_active; p2[c2].ext_dim = 1; p2[c2].c_rowmap = idx;
+        ++c2;
+    }
+    if (dQ) {
+        p2[c2] = {dh, ldh, false, x, ldx, false, dQ, lddq, r, d, n, nullptr};
+        p2[c2].ext = r_active; p2[c2].ext_dim = 1; p2[c2].c_rowmap = idx;
+        ++c2;
+    }
+    if (dx) {
+        p2[c2] = {dh, ldh, true, Q, ldq, false, dx, lddx, n, d, r, nullptr};
+        p2[c2].ext = r_active; p2[c2].ext_dim = 2; p2[c2].b_map = idx; p2[c2].b_map_rows = r;
+        ++c2;
+    }
+    if (c2) { rc = launch_group(dt, p2, c2, st); if (rc != FLOP_OK) return rc; }
+
+    if (dlog_alpha && fused_rows) {
+        const int chunks = (int)((n + fused_rows - 1) / fused_rows);
+        hipLaunchKernelGGL(dalpha_finish_kernel, dim3((unsigned)((r + 31) / 32)), dim3(kStreamThreads), 0, st,
+                           (const float*)partial, chunks, r, zc, dzda_c, dlog_alpha, accumulate, (const int32_t*)nullptr,
+                           fused_rows, r_active, idx);
+        if (hipGetLastError() != hipSuccess) return FLOP_ERR_HIP;
+    } else if (dlog_alpha) {
+        rc = launch_gate_grad(dt, n, r, dh, ldh, g_active, ldg, zc, dzda_c, dlog_alpha, accumulate, partial, st, r_active,
+                              nullptr, idx);
+        if (rc != FLOP_OK) return rc;
+    }
+    return FLOP_OK;
 }
 
 int flop_gather_gates(const float* src, const int32_t* idx, const int32_t* r_active, int64_t r,

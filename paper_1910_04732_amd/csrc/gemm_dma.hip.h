@@ -56,6 +56,12 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // beyond any descriptor we build (ranges < 2 GiB)
+constexpr int kKtabMaxK = 4096;                 // longest contraction over gathered k rows
+constexpr int kKtabBytes = (kKtabMaxK + 256) * 2;   // its table in LDS: 16-bit row numbers, rounded up to a step of 4 groups
+constexpr uint32_t kKtabNone = 0xFFFFu;         // table entry of a k beyond the contraction
+
+template <typename SH>
+constexpr size_t gemm_dma_lds_bytes();
 
 // Swizzle of a [k][row] stage with S 64-byte segments per k row: segment index seg of k row krow is stored at
 // segment kr_swizzle<S>(krow, seg).  Four consecutive k rows (what one transposing fragment read touches per
@@ -80,12 +86,21 @@ struct DmaPlan {
     uint32_t voff[NV];       // byte offset of each transfer at step 0 (kOutOfRange: zero-fill)
     uint32_t tail_bit[NV];   // kOutOfRange where the transfer lies beyond K in the group's last step
     uint32_t step_bytes;     // added per step (scalar offset)
+    // A [k][row] operand whose k rows are gathered through an index list: ktab (LDS) holds the matrix row of
+    // every k of the contraction (kKtabNone beyond K), voff only the column part, kidx[p] the transfer's k
+    // at step 0, and kv[p] the byte offsets of the rows of the step that is issued next, read one step ahead.
+    const uint16_t* ktab;    // nullptr: not gathered
+    uint32_t kidx[NV], kv[NV], kstep, row_bytes;
 
     // kmajor: X[row*ld + k]      otherwise: X[k*ld + row]
     // tid: thread index inside the group; k_first: first k of the group (64 g); k_stride: 64 G; nk: steps
+    // map (nullable): rows (kmajor) are rows map[row] of the matrix; ktab_ (nullable, !kmajor): see ktab
     __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid, int k_first,
-                                         int k_stride, int nk)
+                                         int k_stride, int nk, const int32_t* map = nullptr, const uint16_t* ktab_ = nullptr)
     {
+        ktab = kmajor ? nullptr : ktab_;
+        kstep = (uint32_t)k_stride;
+        row_bytes = (uint32_t)(ld * 2);
         const int wave = tid >> 6, lane = tid & 63;
         const int ktail0 = (nk - 1) * k_stride + k_first;   // first k of the group's last step
 #pragma unroll
@@ -94,8 +109,11 @@ struct DmaPlan {
             if (kmajor) {
                 const int row = pos >> 3, cp = pos & 7;
                 const int c = cp ^ ((row >> 1) & 7);
-                voff[p] = (row0 + row < rows) ? (uint32_t)(((int64_t)(row0 + row) * ld + k_first + c * 8) * 2) : kOutOfRange;
+                const bool inside = row0 + row < rows;
+                const int64_t src_row = (map && inside) ? map[row0 + row] : row0 + row;
+                voff[p] = inside ? (uint32_t)((src_row * ld + k_first + c * 8) * 2) : kOutOfRange;
                 tail_bit[p] = (ktail0 + c * 8 < K) ? 0u : kOutOfRange;
+                kidx[p] = 0; kv[p] = 0;
             } else {
                 constexpr int CPR = ROWS / 8;             // 16-byte chunks per k-row
                 constexpr int S = ROWS / 32;              // 64-byte segments per k-row
@@ -104,11 +122,43 @@ struct DmaPlan {
                 int src_seg = cc >> 2;
                 if constexpr (S == 2 || S == 4 || S == 8) src_seg = kr_swizzle<S>(krow, cc >> 2);   // XOR: its own inverse
                 const int m = row0 + src_seg * 32 + (cc & 3) * 8;
-                voff[p] = (m < rows) ? (uint32_t)(((int64_t)(k_first + krow) * ld + m) * 2) : kOutOfRange;
+                if (ktab) voff[p] = (m < rows) ? (uint32_t)(m * 2) : kOutOfRange;
+                else voff[p] = (m < rows) ? (uint32_t)(((int64_t)(k_first + krow) * ld + m) * 2) : kOutOfRange;
                 tail_bit[p] = 0u;                         // k rows beyond K fail the range check
+                kidx[p] = (uint32_t)(k_first + krow);
+                kv[p] = 0;
             }
         }
         step_bytes = kmajor ? (uint32_t)(k_stride * 2) : (uint32_t)((int64_t)k_stride * ld * 2);
+        if (ktab) step_bytes = 0;
+    }
+
+    // gathered k rows: read the table entries of `step` (the next one to be issued)
+    __device__ __forceinline__ void fetch_k(int step)
+    {
+        if (!ktab) return;
+#pragma unroll
+        for (int p = 0; p < NV; ++p) {
+            const uint32_t row = ktab[(uint32_t)step * kstep + kidx[p]];
+            kv[p] = row == kKtabNone ? kOutOfRange : row * row_bytes;
+        }
+    }
+
+    // Pins the table entries read by fetch_k into registers here: call right after the wait that drains the
+    // wave's LDS reads, so that the compiler's own wait for them lands there and not among the fragment reads.
+    __device__ __forceinline__ void settle_k()
+    {
+        if (!ktab) return;
+#pragma unroll
+        for (int p = 0; p < NV; ++p) asm volatile("" : "+v"(kv[p]));
+    }
+
+    // byte offset of transfer p: the plan's own, or column part + the k row's table entry (either may be out of range)
+    __device__ __forceinline__ uint32_t offset_of(int p, uint32_t tail_mask) const
+    {
+        const uint32_t own = voff[p] | (tail_bit[p] & tail_mask);
+        if (!ktab) return own;
+        return (own + kv[p]) | ((own | kv[p]) & kOutOfRange);
     }
 
     // transfer number p of the plan alone (p is a compile-time constant at every call site)
@@ -116,7 +166,7 @@ struct DmaPlan {
                                               uint32_t tail_mask, int wave) const
     {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * NW + wave) * 1024), 16,
-                                                 voff[p] | (tail_bit[p] & tail_mask), (uint32_t)step * step_bytes, 0, 0);
+                                                 offset_of(p, tail_mask), (uint32_t)step * step_bytes, 0, 0);
     }
 
     __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, unsigned char* stage, int step,
@@ -126,7 +176,7 @@ struct DmaPlan {
 #pragma unroll
         for (int p = 0; p < NV; ++p)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FLOP_LDS_PTR(stage + (p * NW + wave) * 1024), 16,
-                                                     voff[p] | (tail_bit[p] & tail_mask), soff, 0, 0);
+                                                     offset_of(p, tail_mask), soff, 0, 0);
     }
 };
 
@@ -146,8 +196,9 @@ struct DmaPlan4 {
     uint32_t step_bytes;
 
     // same signature as DmaPlan::init; only used by blocks of one group (k_first = 0, k_stride = 64)
+    // (gathered operands are never routed to 4-byte transfers: the last two arguments are ignored)
     __device__ __forceinline__ void init(int kmajor, int64_t ld, int row0, int rows, int K, int tid, int /*k_first*/,
-                                         int /*k_stride*/, int nk)
+                                         int /*k_stride*/, int nk, const int32_t* = nullptr, const uint16_t* = nullptr)
     {
         const int wave = tid >> 6, lane = tid & 63;
         const int ktail0 = (nk - 1) * 64;
@@ -192,6 +243,8 @@ struct DmaPlan4 {
 #pragma unroll
         for (int p = 0; p < NV; ++p) issue_one(p, rsrc, stage, step, tail_mask, wave);
     }
+    __device__ __forceinline__ void fetch_k(int) {}
+    __device__ __forceinline__ void settle_k() {}
 };
 
 // One MFMA operand fragment: 8 bfloat16 (k = 16*kc + 8*(lane/32) + 0..7) of row lane%32,
@@ -332,8 +385,10 @@ struct DmaLoop {
     int kfix, kfix_chunk;   // K % 8 (elements of the chunk that straddles K); that chunk's index in this group's last
                             // step, or -1 if it lies in another group's
 
-    // group: index of this wavefront's group; smem_: start of the block's dynamic LDS
-    __device__ __forceinline__ void init(const GemmProblem& pr, unsigned char* smem_, int m0, int n0, int group)
+    // group: index of this wavefront's group; smem_: start of the block's dynamic LDS; ktab: the table of k-row
+    // offsets in LDS when B is a [k][row] operand gathered by pr.b_map (filled by the caller), else nullptr
+    __device__ __forceinline__ void init(const GemmProblem& pr, unsigned char* smem_, int m0, int n0, int group,
+                                         const uint16_t* ktab)
     {
         const int tid = threadIdx.x % (64 * SH::NWG);
         const int lane = tid & 63;
@@ -346,9 +401,11 @@ struct DmaLoop {
         // its range stays small however large the matrix is; a [k][row] operand's covers the k range.
         const int a_rows = min(BM, pr.M - m0), b_rows = min(BN, pr.N - n0);
         const int64_t a_elems = AKM ? ((int64_t)(a_rows - 1) * pr.lda + K8) : ((int64_t)(pr.K - 1) * pr.lda + M8);
-        const int64_t b_elems = BKM ? ((int64_t)(b_rows - 1) * pr.ldb + K8) : ((int64_t)(pr.K - 1) * pr.ldb + N8);
+        // a gathered B is described whole: any of the matrix's rows may be asked for
+        const int64_t b_elems = pr.b_map ? ((int64_t)(pr.b_map_rows - 1) * pr.ldb + (BKM ? K8 : N8))
+                                         : BKM ? ((int64_t)(b_rows - 1) * pr.ldb + K8) : ((int64_t)(pr.K - 1) * pr.ldb + N8);
         const uint16_t* a_base = (const uint16_t*)pr.A + (AKM ? (int64_t)m0 * pr.lda : 0);
-        const uint16_t* b_base = (const uint16_t*)pr.B + (BKM ? (int64_t)n0 * pr.ldb : 0);
+        const uint16_t* b_base = (const uint16_t*)pr.B + ((BKM && !pr.b_map) ? (int64_t)n0 * pr.ldb : 0);
         ra = __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, (int)(a_elems * 2), 0x00020000);
         rb = __builtin_amdgcn_make_buffer_rsrc((void*)b_base, 0, (int)(b_elems * 2), 0x00020000);
         constexpr int KS = 64 * SH::G;
@@ -357,7 +414,11 @@ struct DmaLoop {
         // rows of a [row][k] operand beyond the tile (stage rows that only pad the tile included) lie beyond the
         // descriptor; of a [k][row] operand they are tested against the matrix
         pa.init(AKM, pr.lda, AKM ? 0 : m0, AKM ? min(BM, pr.M - m0) : min(pr.M, m0 + BM), pr.K, tid, k_first, KS, nk);
-        pb.init(BKM, pr.ldb, BKM ? 0 : n0, BKM ? min(BN, pr.N - n0) : min(pr.N, n0 + BN), pr.K, tid, k_first, KS, nk);
+        if (pr.b_map && BKM)   // rows n0 .. of the product are rows b_map[n0 ..] of the matrix
+            pb.init(true, pr.ldb, n0, min(pr.N, n0 + BN), pr.K, tid, k_first, KS, nk, pr.b_map, nullptr);
+        else
+            pb.init(BKM, pr.ldb, BKM ? 0 : n0, BKM ? min(BN, pr.N - n0) : min(pr.N, n0 + BN), pr.K, tid, k_first, KS, nk,
+                    nullptr, ktab);
         fa.init(wm * SH::WTM, lane);
         fb.init(wn * SH::WTN, lane);
         smem = smem_ + group * SH::GROUP_BYTES;
@@ -369,6 +430,7 @@ struct DmaLoop {
         kfix_chunk = (straddle >= last0 && straddle < last0 + 64) ? ((straddle - last0) >> 3) : -1;
     }
 
+    // (a gathered B must have had its table entries of `step` fetched: pb.fetch_k)
     __device__ __forceinline__ void issue(int step) const
     {
         unsigned char* st = smem + (step % NB) * STAGE;
@@ -428,15 +490,19 @@ struct DmaLoop {
     }
 
     __device__ __forceinline__ void iterate(int s, FragSet<TM, TN>& cur, FragSet<TM, TN>& nxt,
-                                            f32x16 (&acc)[TM][TN]) const
+                                            f32x16 (&acc)[TM][TN])
     {
         wait_fragset<TM, TN>(cur);
+        pb.settle_k();
         if (s + 1 < nk) {
             // younger stages already issued: s+2 .. min(nk-1, s+NB-1)
             const int last = (nk - 1 < s + NB - 1) ? nk - 1 : s + NB - 1;
             wait_stage(last - (s + 1));
             __builtin_amdgcn_s_barrier();   // stage s+1 is complete in LDS; nobody still reads stage s
-            if (s + NB < nk) issue(s + NB);
+            if (s + NB < nk) {
+                issue(s + NB);
+                if (s + NB + 1 < nk) pb.fetch_k(s + NB + 1);
+            }
             fix_ktail(s + 1);
             read(s + 1, nxt);
         }
@@ -506,23 +572,26 @@ struct DmaLoop {
     // valid while s + NB < nk - 1: every conditional of iterate() is taken and the
     // transfers issued are not the (possibly partial) last step
     __device__ __forceinline__ void iterate_steady(int s, FragSet<TM, TN>& cur, FragSet<TM, TN>& nxt,
-                                                   f32x16 (&acc)[TM][TN]) const
+                                                   f32x16 (&acc)[TM][TN])
     {
         wait_fragset<TM, TN>(cur);
+        pb.settle_k();                  // table entries of step s+NB (gathered B), read during the last iteration
         wait_stage(NB - 2);             // stages s+2 .. s+NB-1 may still be in flight
         __builtin_amdgcn_s_barrier();   // stage s+1 is complete in LDS; nobody still reads stage s
         const uint32_t sa = smem_addr + (uint32_t)(((s + 1) % NB) * STAGE);
         unsigned char* st = smem + ((s + NB) % NB) * STAGE;
         __builtin_amdgcn_sched_barrier(0);
         slots(s, sa, sa + A_BYTES, st, 0u, cur, nxt, acc, std::make_integer_sequence<int, NMMA>{});
+        pb.fetch_k(s + NB + 1);         // in range: s + NB < nk - 1 here
     }
 
-    __device__ __forceinline__ void run(f32x16 (&acc)[TM][TN]) const
+    __device__ __forceinline__ void run(f32x16 (&acc)[TM][TN])
     {
         FragSet<TM, TN> f0, f1;
 #pragma unroll
         for (int s = 0; s < NB; ++s)
-            if (s < nk) issue(s);
+            if (s < nk) { pb.fetch_k(s); issue(s); }
+        if (NB < nk) pb.fetch_k(NB);
         wait_stage((nk - 1 < NB - 1) ? nk - 1 : NB - 1);
         __builtin_amdgcn_s_barrier();
         fix_ktail(0);
@@ -541,10 +610,10 @@ struct DmaLoop {
 
 template <typename SH, bool AKM, bool BKM, int XFER>
 __device__ __forceinline__ void dma_main_loop(const GemmProblem& pr, unsigned char* smem, int m0, int n0, int group,
-                                              f32x16 (&acc)[SH::TM][SH::TN])
+                                              const uint16_t* ktab, f32x16 (&acc)[SH::TM][SH::TN])
 {
     DmaLoop<SH, AKM, BKM, XFER> loop;
-    loop.init(pr, smem, m0, n0, group);
+    loop.init(pr, smem, m0, n0, group, ktab);
     loop.run(acc);
 }
 
@@ -583,8 +652,22 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(const GemmGr
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    if (pr.a_kmajor) dma_main_loop<SH, true, BKM, XFER>(pr, smem, m0, n0, group, acc);
-    else dma_main_loop<SH, false, BKM, XFER>(pr, smem, m0, n0, group, acc);
+    // B gathered along k: the matrix rows of its k rows go to a table behind the block's other LDS (block-uniform
+    // condition; the host has checked K <= kKtabMaxK and fewer than 65535 rows)
+    const uint16_t* ktab = nullptr;
+    if constexpr (!BKM && XFER == 16) {
+        if (pr.b_map) {
+            uint16_t* tab = (uint16_t*)(smem + gemm_dma_lds_bytes<SH>());
+            constexpr int KS = 64 * SH::G;
+            const int entries = (pr.K + KS - 1) / KS * KS;
+            for (int k = tid; k < entries; k += THREADS)
+                tab[k] = (uint16_t)(k < pr.K ? (uint32_t)pr.b_map[k] : kKtabNone);
+            __syncthreads();
+            ktab = tab;
+        }
+    }
+    if (pr.a_kmajor) dma_main_loop<SH, true, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
+    else dma_main_loop<SH, false, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
     __syncthreads();
 
     // ---- the groups' partial sums are added in group order (fixed, so the result is deterministic): groups

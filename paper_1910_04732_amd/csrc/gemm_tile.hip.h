@@ -72,6 +72,11 @@ struct GemmProblem {
     int64_t lddot;
     float* dot_partial;       // tiles_m rows of dot_ld floats
     int64_t dot_ld;           // the host's N (a device-side extent does not change the row pitch)
+    // Optional gather of B by an index list (the open components of a layer, ascending): the product runs on the
+    // rows b_map[0 .. extent) of the b_map_rows-row matrix at B - its rows n when b_kmajor (B[n][k] = matrix row
+    // b_map[n]), its k rows otherwise (B[k][n] = matrix row b_map[k]).  No compacted copy of the matrix is needed.
+    const int32_t* b_map;
+    int b_map_rows;
 };
 
 struct GemmGroup {
@@ -156,15 +161,16 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
     return __builtin_bit_cast(float, b << 16);
 }
 
-// 16 bytes of `base[row*ld + col ...]`, zero where row >= rows or col+e >= cols.
+// 16 bytes of `base[src_row*ld + col ...]` (src_row: where row lies in memory, row itself unless the operand is
+// gathered), zero where row >= rows or col+e >= cols.
 template <int ES>
 __device__ __forceinline__ u32x4 load_vec16(const void* base, int64_t ld, int row, int col,
-                                            int rows, int cols, bool vec_ok)
+                                            int rows, int cols, bool vec_ok, int src_row)
 {
     constexpr int E = 16 / ES;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (row < rows && col < cols) {
-        const char* p = (const char*)base + ((int64_t)row * ld + col) * ES;
+        const char* p = (const char*)base + ((int64_t)src_row * ld + col) * ES;
         if (vec_ok && col + E <= cols) {
             v = *(const u32x4*)p;
         } else if constexpr (ES == 2) {
@@ -193,19 +199,26 @@ struct TileStager {
     static constexpr int VPR = ROWS * ES / 16;   // vectors per k-row when rows are contiguous
     u32x4 v[NV];
 
+    // map (nullable): the operand's rows (kmajor) or k rows (otherwise) are rows map[i] of the matrix at base
     __device__ __forceinline__ void load(const void* base, int64_t ld, int kmajor, bool vec_ok,
-                                         int row0, int k0, int rows, int K, int tid)
+                                         int row0, int k0, int rows, int K, int tid, const int32_t* map = nullptr)
     {
         if (kmajor) {
             const int c = tid & 7, r0 = tid >> 3;
 #pragma unroll
-            for (int p = 0; p < NV; ++p)
-                v[p] = load_vec16<ES>(base, ld, row0 + r0 + 32 * p, k0 + c * E, rows, K, vec_ok);
+            for (int p = 0; p < NV; ++p) {
+                const int row = row0 + r0 + 32 * p;
+                const int src = (map && row < rows) ? map[row] : row;
+                v[p] = load_vec16<ES>(base, ld, row, k0 + c * E, rows, K, vec_ok, src);
+            }
         } else {
             const int mv = tid % VPR, kq = tid / VPR;
 #pragma unroll
-            for (int q = 0; q < NV; ++q)
-                v[q] = load_vec16<ES>(base, ld, k0 + kq * NV + q, row0 + mv * E, K, rows, vec_ok);
+            for (int q = 0; q < NV; ++q) {
+                const int k = k0 + kq * NV + q;
+                const int src = (map && k < K) ? map[k] : k;
+                v[q] = load_vec16<ES>(base, ld, k, row0 + mv * E, K, rows, vec_ok, src);
+            }
         }
     }
 
@@ -301,7 +314,7 @@ __global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(const GemmG
     const int nk = ((pr.K + BK - 1) / BK + G - 1) / G;
 
     sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, group * BK, pr.M, pr.K, tid);
-    sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, group * BK, pr.N, pr.K, tid);
+    sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, group * BK, pr.N, pr.K, tid, pr.b_map);
     sa.store(gmem, pr.a_kmajor, tid);
     sb.store(gmem + A_BYTES, pr.b_kmajor, tid);
     __syncthreads();
@@ -312,7 +325,7 @@ __global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(const GemmG
         const bool more = (s + 1 < nk);
         if (more) {
             sa.load(pr.A, pr.lda, pr.a_kmajor, pr.a_vec != 0, m0, ((s + 1) * G + group) * BK, pr.M, pr.K, tid);
-            sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, ((s + 1) * G + group) * BK, pr.N, pr.K, tid);
+            sb.load(pr.B, pr.ldb, pr.b_kmajor, pr.b_vec != 0, n0, ((s + 1) * G + group) * BK, pr.N, pr.K, tid, pr.b_map);
         }
         const unsigned char* la = cur + (wm * WTM + l32) * kLdsRow + lhi * 16;
         const unsigned char* lb = cur + A_BYTES + (wn * WTN + l32) * kLdsRow + lhi * 16;

@@ -355,7 +355,8 @@ __global__ __launch_bounds__(kGateL0Threads) void gate_l0_kernel(
 __device__ __forceinline__ void dalpha_finish_block(
     int block, const float* __restrict__ partial, int chunks, int64_t r, const float* __restrict__ z,
     const float* __restrict__ dzda, float* __restrict__ dlog_alpha, int accumulate,
-    const int32_t* __restrict__ seg, int chunk_rows, const int32_t* __restrict__ r_active)
+    const int32_t* __restrict__ seg, int chunk_rows, const int32_t* __restrict__ r_active,
+    const int32_t* __restrict__ out_map = nullptr)   // nullable: gate k's result goes to dlog_alpha[out_map[k]], k < r_active
 {
     __shared__ double red[8][33];
     if (seg) chunks = (seg[1] + chunk_rows - 1) / chunk_rows;
@@ -375,16 +376,18 @@ __device__ __forceinline__ void dalpha_finish_block(
         const float zk = z[k], dk = dzda[k];
         float res = 0.0f;
         if (k < r_used && zk != 0.0f && dk != 0.0f) res = (float)(tot / ((double)zk * (double)zk) * (double)dk);
-        dlog_alpha[k] = accumulate ? dlog_alpha[k] + res : res;
+        if (!out_map) dlog_alpha[k] = accumulate ? dlog_alpha[k] + res : res;
+        else if (k < r_used) { const int o = out_map[k]; dlog_alpha[o] = accumulate ? dlog_alpha[o] + res : res; }
     }
 }
 
 __global__ __launch_bounds__(kStreamThreads) void dalpha_finish_kernel(
     const float* __restrict__ partial, int chunks, int64_t r, const float* __restrict__ z,
     const float* __restrict__ dzda, float* __restrict__ dlog_alpha, int accumulate,
-    const int32_t* __restrict__ seg, int chunk_rows, const int32_t* __restrict__ r_active)
+    const int32_t* __restrict__ seg, int chunk_rows, const int32_t* __restrict__ r_active,
+    const int32_t* __restrict__ out_map)
 {
-    dalpha_finish_block((int)blockIdx.x, partial, chunks, r, z, dzda, dlog_alpha, accumulate, seg, chunk_rows, r_active);
+    dalpha_finish_block((int)blockIdx.x, partial, chunks, r, z, dzda, dlog_alpha, accumulate, seg, chunk_rows, r_active, out_map);
 }
 
 // Up to sixteen gate vectors (the clusters of an adaptive embedding, the layers of a model) in one launch:
@@ -696,6 +699,36 @@ __global__ __launch_bounds__(kStreamThreads) void gather_gates_kernel(
 {
     const int rp = r_active[0];
     for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < rp; j += gridDim.x * kStreamThreads) dst[j] = src[idx[j]];
+}
+
+__device__ __forceinline__ int active_slot(const int32_t* __restrict__ idx, int rp, int k);
+
+// Block k (one per component): if k is not in the ascending list idx[0 .. r_active) it is closed, and row k of the
+// two gradients a (cols_a columns) and b (cols_b columns), elements of es bytes, and gate[k] are set to zero
+// (each output nullable).  The open rows are written by the contractions themselves.
+__global__ __launch_bounds__(kStreamThreads) void zero_closed_rows_kernel(
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ r_active, int r,
+    void* __restrict__ a, int64_t lda, int cols_a, void* __restrict__ b, int64_t ldb, int cols_b, int es,
+    float* __restrict__ gate)
+{
+    const int k = blockIdx.x;
+    if (k >= r || active_slot(idx, min(r, r_active[0]), k) >= 0) return;
+    if (gate && threadIdx.x == 0) gate[k] = 0.0f;
+    void* rows[2] = {a, b};
+    const int64_t lds_[2] = {lda, ldb};
+    const int cols[2] = {cols_a, cols_b};
+    for (int q = 0; q < 2; ++q) {
+        if (!rows[q]) continue;
+        char* dst = (char*)rows[q] + (int64_t)k * lds_[q] * es;
+        const int64_t bytes = (int64_t)cols[q] * es;
+        if ((((uintptr_t)dst) & 15u) == 0) {
+            for (int64_t o = (int64_t)threadIdx.x * 16; o + 16 <= bytes; o += (int64_t)kStreamThreads * 16)
+                *(uint4*)(dst + o) = uint4{0u, 0u, 0u, 0u};
+            for (int64_t o = bytes / 16 * 16 + threadIdx.x; o < bytes; o += kStreamThreads) dst[o] = 0;
+        } else {
+            for (int64_t o = threadIdx.x; o < bytes; o += kStreamThreads) dst[o] = 0;
+        }
+    }
 }
 
 // Position of k in the ascending list idx[0..rp), or -1.

@@ -118,7 +118,11 @@ def lib():
         L.flop_active_prepare.argtypes = ([_int] + [_i64] * 3 + [_vp, _vp, flop_hc, _vp, _i64, _vp, _i64,
                                           _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp])
         L.flop_active_prepare.restype = _int
-        for name in ("flop_fwd_active", "flop_bwd_active", "flop_gather_gates", "flop_expand_grads"):
+        L.flop_fwd_active_indexed.argtypes = ([_int] + [_i64] * 4 + [_vp, _i64] * 3 + [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp])
+        L.flop_bwd_active_indexed.argtypes = ([_int] + [_i64] * 4 + [_vp, _i64] * 4 + [_vp, _vp, _vp, _vp, _vp, _i64]
+                                              + [_vp, _i64] * 3 + [_vp, _int, _vp, _sz, _vp])
+        for name in ("flop_fwd_active", "flop_bwd_active", "flop_gather_gates", "flop_expand_grads",
+                     "flop_fwd_active_indexed", "flop_bwd_active_indexed"):
             getattr(L, name).restype = _int
         L.flop_bench_force_tile_shape.argtypes = [_int]
         L.flop_bench_force_tile_shape.restype = _int
@@ -394,20 +398,63 @@ def flop_bwd_active(dy, x, Qc, Pc, zc, dzda_c, r_active, g_saved, dx, dQc, dPc, 
 
 
 def flop_active_prepare(log_alpha, u, hc: flop_hc, Q, P, z, dzda, r_active, idx, Qc, Pc, zc, dzda_c, stream=None):
-    """Gate sampling + compaction of Q, P + gather of dz/dalpha for one training step (two launches)."""
+    """Gate sampling + compaction of Q, P + gather of dz/dalpha for one training step (two launches; one with
+    ``Qc = Pc = None``, which leaves only the index list, the gates and their gathers: what the indexed calls need)."""
     dt = _dt(Q)
     r, d = Q.shape
-    dout = P.shape[0]
-    assert P.shape == (dout, r) and log_alpha.numel() == r
+    dout = P.shape[0] if P is not None else 0
+    assert (P is None or P.shape == (dout, r)) and log_alpha.numel() == r
     qp, ldq = _mat(Q, "Q")
-    pp, ldp = _mat(P, "P")
-    qcp, ldqc = _mat(Qc, "Qc")
-    pcp, ldpc = _mat(Pc, "Pc")
+    pp, ldp = (None, 0) if P is None else _mat(P, "P")
+    qcp, ldqc = (None, 0) if Qc is None else _mat(Qc, "Qc")
+    pcp, ldpc = (None, 0) if Pc is None else _mat(Pc, "Pc")
     _check(lib().flop_active_prepare(dt, d, r, dout, _vec(log_alpha, "log_alpha"), _vec(u, "u"), hc, qp, ldq, pp, ldp,
                                      _vec(z, "z"), _vec(dzda, "dzda"), _vec(r_active, "r_active", torch.int32),
                                      _vec(idx, "idx", torch.int32), qcp, ldqc, pcp, ldpc, _vec(zc, "zc"),
                                      _vec(dzda_c, "dzda_c"), _stream(stream)), "flop_active_prepare")
     return r_active, idx
+
+
+def flop_fwd_active_indexed(x, Q, Pt, zc, idx, r_active, g_active, y, stream=None):
+    """Forward on the open components read in place: Q[r, d], Pt[r, dout] (P transposed), index list from
+    flop_active_prepare / flop_compact; g_active[n, r] receives the first r_active columns."""
+    dt = _dt(x)
+    n, d = x.shape
+    r, dout = Pt.shape
+    assert Q.shape == (r, d) and g_active.shape == (n, r) and y.shape == (n, dout)
+    xp, ldx = _mat(x, "x")
+    qp, ldq = _mat(Q, "Q")
+    pp, ldpt = _mat(Pt, "Pt")
+    gp, ldg = _mat(g_active, "g_active")
+    yp, ldy = _mat(y, "y")
+    _check(lib().flop_fwd_active_indexed(dt, n, d, r, dout, xp, ldx, qp, ldq, pp, ldpt, _vec(zc, "zc"),
+                                         _vec(idx, "idx", torch.int32), _vec(r_active, "r_active", torch.int32),
+                                         gp, ldg, yp, ldy, _stream(stream)), "flop_fwd_active_indexed")
+    return y
+
+
+def flop_bwd_active_indexed(dy, x, Q, Pt, zc, dzda_c, idx, r_active, g_active, dx, dQ, dPt, dlog_alpha, ws,
+                            accumulate=False, stream=None):
+    """Backward on the open components read in place; full-size dQ[r, d], dPt[r, dout], dlog_alpha[r] with exact
+    zeros for the closed components."""
+    dt = _dt(x)
+    n, d = x.shape
+    r, dout = Pt.shape
+    assert dy.shape == (n, dout) and Q.shape == (r, d) and g_active.shape == (n, r)
+    dyp, lddy = _mat(dy, "dy")
+    xp, ldx = _mat(x, "x")
+    qp, ldq = _mat(Q, "Q")
+    pp, ldpt = _mat(Pt, "Pt")
+    gp, ldg = _mat(g_active, "g_active")
+    dxp, lddx = (None, 0) if dx is None else _mat(dx, "dx")
+    dqp, lddq = (None, 0) if dQ is None else _mat(dQ, "dQ")
+    dpp, lddpt = (None, 0) if dPt is None else _mat(dPt, "dPt")
+    _check(lib().flop_bwd_active_indexed(dt, n, d, r, dout, dyp, lddy, xp, ldx, qp, ldq, pp, ldpt,
+                                         _vec(zc, "zc"), _vec(dzda_c, "dzda_c"), _vec(idx, "idx", torch.int32),
+                                         _vec(r_active, "r_active", torch.int32), gp, ldg, dxp, lddx, dqp, lddq, dpp, lddpt,
+                                         _vec(dlog_alpha, "dlog_alpha"), 1 if accumulate else 0,
+                                         _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)), "flop_bwd_active_indexed")
+    return dx, dQ, dPt, dlog_alpha
 
 
 def flop_gather_gates(src, idx, r_active, dst, stream=None):

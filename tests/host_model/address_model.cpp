@@ -5,7 +5,8 @@
 //
 //   address_model random <seed> <cases>     layers of random shape in every alignment class, 1-4 per case, gate
 //                                           vectors sliced at arbitrary offsets out of one array: plain calls, then
-//                                           flop_fwd_sampling / flop_bwd_deferred / flop_bwd_boundary
+//                                           flop_fwd_sampling / flop_bwd_deferred / flop_bwd_boundary, then the
+//                                           indexed active-rank calls (gathered rows, scattered output rows)
 //   address_model classes [stride]          a fixed sweep (every stride-th case of it): every combination of alignment class of d, r, dout
 //                                           (odd, 2 mod 4, 4 mod 8, 0 mod 8) with dense last rows, riders on
 //                                           and off, empty pending lists, boundary jobs with and without new gates
@@ -140,6 +141,29 @@ void riding_pass(flop_dtype dt, std::vector<Layer>& layers, int64_t G, const flo
     }
 }
 
+// The open components read in place (flop_fwd_active_indexed / flop_bwd_active_indexed): every third component
+// closed, the index list written here (the scan kernel's values are not modelled), P held transposed.  Rows of
+// Q and Pt gathered by the list, output rows of dQ and dPt scattered by it, closed rows zeroed.
+void indexed_pass(flop_dtype dt, std::vector<Layer>& layers)
+{
+    const size_t es = dt == FLOP_BF16 ? 2 : 4;
+    for (Layer& t : layers) {
+        Buf idx((size_t)t.r * 4), r_act(4), zc = gates(t.r, 0.5f), dzc = gates(t.r, 0.1f);
+        int32_t cnt = 0;
+        for (int64_t k = 0; k < t.r; ++k)
+            if (k % 3 != 1) ((int32_t*)idx.p)[cnt++] = (int32_t)k;
+        *(int32_t*)r_act.p = cnt;
+        Buf Pt((size_t)t.r * t.dout * es), dPt((size_t)t.r * t.dout * es);
+        must(flop_fwd_active_indexed(dt, t.n, t.d, t.r, t.dout, t.x.p, t.d, t.Q.p, t.d, Pt.p, t.dout, zc.f(),
+                                     (const int32_t*)idx.p, (const int32_t*)r_act.p, t.g.p, t.r, t.y.p, t.dout, nullptr),
+             "flop_fwd_active_indexed");
+        must(flop_bwd_active_indexed(dt, t.n, t.d, t.r, t.dout, t.dy.p, t.dout, t.x.p, t.d, t.Q.p, t.d, Pt.p, t.dout, zc.f(),
+                                     dzc.f(), (const int32_t*)idx.p, (const int32_t*)r_act.p, t.g.p, t.r, t.dx.p, t.d,
+                                     t.dQ.p, t.d, dPt.p, t.dout, t.da.f(), 0, t.ws.p, t.ws.bytes, nullptr),
+             "flop_bwd_active_indexed");
+    }
+}
+
 void run_case(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, int64_t extra, bool next_gates)
 {
     std::vector<Layer> layers;
@@ -149,6 +173,7 @@ void run_case(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, 
     Buf la = gates(G, 0.3f), u = gates(G, 0.4f), w = gates(G, 2.0f);
     plain_pass(dt, layers, G, la.f(), u.f(), w.f());
     riding_pass(dt, layers, G, la.f(), u.f(), w.f(), next_gates);
+    indexed_pass(dt, layers);
 }
 
 std::string describe(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, int64_t extra, bool next_gates)

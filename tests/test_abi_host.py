@@ -36,6 +36,29 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), f"{name} declared in include/*.h but not exported"
 
 
+def test_every_entry_point_has_declared_argument_types(lib):
+    """A foreign function without argtypes gets Python ints as 32-bit C ints: a 64-bit size or leading dimension
+    that travels on the stack then arrives with an undefined upper half (a wild row pitch inside a kernel)."""
+    for name in _declared():
+        fn = getattr(lib, name)
+        if name in ("flop_bench_tile_shapes",):   # no parameters
+            continue
+        assert fn.argtypes is not None, f"flop.py declares no argtypes for {name}"
+
+
+def test_oversized_leading_dimensions_are_rejected(lib):
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    big = (1 << 32) + 4                    # what a 32-bit 4 with a garbage upper half looks like
+    L = lib
+    assert L.flop_fwd(0, 2, 4, 4, 4, p, big, p, 4, p, 4, p, p, 4, p, 4, None, 0, None) == -3
+    assert L.flop_fwd(0, 2, 4, 4, 4, p, 4, p, 4, p, 4, p, p, 4, p, big, None, 0, None) == -3
+    assert L.flop_bwd(1, 2, 4, 4, 4, p, 4, p, 4, p, big, p, 4, p, p, p, 4, p, 4, p, 4, p, 4, p, 0, p, 1 << 20, None) == -3
+    assert L.flop_fwd_active_indexed(0, 2, 4, 4, 4, p, 4, p, 4, p, big, p, p, p, p, 4, p, 4, None) == -3
+    assert L.flop_bwd_active_indexed(1, 2, 4, 4, 4, p, 4, p, 4, p, 4, p, 4, p, p, p, p, p, 4,
+                                     p, big, p, 4, p, 4, p, 0, p, 1 << 20, None) == -3
+
+
 def test_status_strings(lib):
     seen = {flop.status_string(s) for s in range(0, -10, -1)}
     assert len(seen) == 10 and flop.status_string(0) == "ok"

@@ -89,3 +89,104 @@ def test_active_rank_all_open_and_all_closed():
     assert got["r_active"] == 48
     got = check(c, log_alpha=np.full(48, -9.0))
     assert got["r_active"] == 0 and np.all(got["y"] == 0) and np.all(got["dx"] == 0)
+
+
+# ------------------------------------------------- open components read in place (no compacted copies) ---
+def run_indexed(c, log_alpha=None, align=0, accumulate=False):
+    """Gates + index list in one launch, then forward and backward on Q[idx], Pt[idx] read in place."""
+    dt = c["dtype"]
+    tdt = TORCH_DT[dt]
+    n, d, r, dout = c["n"], c["d"], c["r"], c["dout"]
+    ld = (lambda cols: -(-cols // align) * align) if align else (lambda cols: cols)
+
+    def mat(a):   # device copy with padded rows (junk in the padding)
+        a = np.asarray(a)
+        buf = torch.full((a.shape[0], ld(a.shape[1])), 7.0, dtype=tdt, device=dev())
+        buf[:, : a.shape[1]] = to_dev(a, dt)
+        return buf[:, : a.shape[1]]
+
+    junk = lambda rows, cols: torch.full((rows, ld(cols)), 3.0, dtype=tdt, device=dev())[:, :cols]
+    x, Q, dy = mat(c["x"]), mat(c["Q"]), mat(c["dy"])
+    Pt = mat(np.ascontiguousarray(c["P"].T))
+    la = to_dev(c["log_alpha"] if log_alpha is None else log_alpha)
+    u = to_dev(c["u"])
+    z, dzda = torch.empty_like(la), torch.empty_like(la)
+    r_act = torch.full((1,), -1, dtype=torch.int32, device=dev())
+    idx = torch.full((r,), -1, dtype=torch.int32, device=dev())
+    zc, dzc = torch.full((r,), 3.0, device=dev()), torch.full((r,), 3.0, device=dev())
+    flop.flop_active_prepare(la, u, hc_struct(), Q, None, z, dzda, r_act, idx, None, None, zc, dzc)
+    g, y = junk(n, r), junk(n, dout)
+    flop.flop_fwd_active_indexed(x, Q, Pt, zc, idx, r_act, g, y)
+    dx, dQ, dPt = junk(n, d), junk(r, d), junk(r, dout)
+    da = torch.full((r,), 3.0, device=dev())
+    ws = flop.workspace(flop.flop_workspace_bytes(flop.FLOP_OP_BWD, flop._dt(x), n, d, r, dout), dev())
+    flop.flop_bwd_active_indexed(dy, x, Q, Pt, zc, dzc, idx, r_act, g, dx, dQ, dPt, da, ws, accumulate=accumulate)
+    torch.cuda.synchronize()
+    return dict(z=to_np(z), r_active=int(r_act.item()), y=to_np(y), dx=to_np(dx), dQ=to_np(dQ), dP=to_np(dPt).T,
+                dalpha=to_np(da) - (3.0 if accumulate else 0.0))
+
+
+def check_indexed(c, log_alpha=None, align=0, accumulate=False):
+    la = c["log_alpha"] if log_alpha is None else log_alpha
+    got = run_indexed(c, log_alpha, align, accumulate)
+    z, dzda = oracle.gate_sample(la, c["u"], BETA, L, R)
+    _, _, y = oracle.fwd(c["x"], c["Q"], c["P"], z)
+    b = oracle.bwd(c["dy"], c["x"], c["Q"], c["P"], z, dzda)
+    assert got["r_active"] == int(np.count_nonzero(z > 0))
+    tol = TOL[c["dtype"]]
+    assert_close(got["y"], y, tol, "y")
+    for k in ("dx", "dQ", "dP", "dalpha"):
+        assert_close(got[k], b[k], tol if not (accumulate and k == "dalpha") else max(tol, 2e-5), k)
+    closed = np.flatnonzero(z == 0)
+    assert np.all(got["dQ"][closed] == 0) and np.all(got["dP"][:, closed] == 0) and np.all(got["dalpha"][closed] == 0)
+    return got
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,align", [((200, 96, 80, 136), 0), ((333, 50, 41, 123), 0), ((130, 264, 136, 72), 8),
+                                         ((333, 75, 141, 523), 8), ((520, 1032, 200, 136), 64), ((70, 9, 3, 5), 8)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else f"align{v}")
+def test_indexed_active_rank_layer_shapes(dtype, shape, align):
+    """Dense rows (register-staged kernel) and 16-byte / 128-byte aligned rows (transfer kernel: gathered rows of a
+    k-contiguous operand, gathered k rows of a [k][row] operand, scattered output rows), ragged everywhere."""
+    n, d, r, dout = shape
+    c = synth.layer_inputs(1900 + n + d, n, d, r, dout, dtype, -1.0, 2.0)   # about half of the gates closed
+    got = check_indexed(c, align=align)
+    assert 0 < got["r_active"] < r
+
+
+def test_indexed_active_rank_matches_the_copying_path_bit_for_bit():
+    c = synth.layer_inputs(1977, 300, 200, 136, 264, "bf16", -1.0, 2.0)
+    a, b = run_active(c, fused_prepare=True), run_indexed(c, align=8)
+    for k in ("z", "y", "dx"):
+        assert np.array_equal(a[k], b[k]), k
+    for k in ("dQ", "dP", "dalpha"):   # same products, possibly another tile shape: summation order may differ
+        assert_close(b[k], a[k], 1e-2, k)
+
+
+def test_indexed_active_rank_c2_half_closed_full_size():
+    for layer in (0, 1):
+        got = check_indexed(synth.config_c2(layer, closed_half=True))
+        assert 0.4 * 768 < got["r_active"] < 0.6 * 768
+
+
+def test_indexed_active_rank_all_open_all_closed_and_accumulate():
+    c = synth.layer_inputs(78, 150, 72, 48, 88, "bf16")
+    got = check_indexed(c, log_alpha=np.full(48, 9.0), align=8)
+    assert got["r_active"] == 48
+    got = check_indexed(c, log_alpha=np.full(48, -9.0), align=8)
+    assert got["r_active"] == 0 and np.all(got["y"] == 0) and np.all(got["dx"] == 0)
+    check_indexed(synth.layer_inputs(79, 150, 72, 48, 88, "bf16", -1.0, 2.0), align=8, accumulate=True)
+
+
+@pytest.fixture
+def forced_shape(request):
+    flop.flop_bench_force_tile_shape(request.param)
+    yield request.param
+    flop.flop_bench_force_tile_shape(-1)
+
+
+@pytest.mark.parametrize("forced_shape", list(range(14)), indirect=True)
+def test_indexed_active_rank_every_block_shape(forced_shape):
+    """The gathered operands under every block shape of the transfer kernel (k groups, 96-wide and 256-row tiles)."""
+    check_indexed(synth.layer_inputs(2100, 333, 264, 200, 392, "bf16", -1.0, 2.0), align=8)
