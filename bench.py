@@ -252,6 +252,9 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
     gate = lambda t: flop.flop_gate_sample(t["la"], t["u"], hc, flop.FLOP_GATE_TRAIN, t["z"], t["dzda"])
     lflops = lambda t: 2.0 * t["n"] * t["r"] * (t["d"] + t["dout"])
 
+    def align_of(t):   # elements a row of x is padded to (1: dense)
+        return 64 if t["x"].stride(0) % 64 == 0 else 8 if t["x"].stride(0) % 8 == 0 else 1
+
     def active_rank_case(name, ls, fl, iters):
         """The same step on the open components only: compact the factors to the sampled mask, run on the
         survivors (their count stays on the device), scatter the gradients back."""
@@ -279,6 +282,24 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
         emit(name, "active ranks only: gate + compact + fwd + bwd + scatter back", t_act, 3 * fl_act, open_ranks=ra,
              dense_equivalent_TFLOP_per_s=round(3 * fl / t_act / 1e12, 1))
         emit(name, "active ranks only: gate + compact + gather (per step overhead)", timeit(lambda: [prep(t) for t in ls], iters))
+
+        # the same step with the open components read in place: P held transposed, no compacted copies, gradients
+        # written through the index list (one launch of preparation: gates, index list, gate gathers)
+        for t in ls:
+            t.update(Pt=empty(t["r"], t["dout"], t["P"].dtype, -(-t["dout"] // align_of(t)) * align_of(t)))
+            t["Pt"].copy_(t["P"].t())
+            t.update(dPt=like(t["Pt"]))
+
+        def prep_i(t):
+            flop.flop_active_prepare(t["la"], t["u"], hc, t["Q"], None, t["z"], t["dzda"], t["r_act"], t["idx"],
+                                     None, None, t["zc"], t["dzc"])
+
+        ifwd = lambda t: flop.flop_fwd_active_indexed(t["x"], t["Q"], t["Pt"], t["zc"], t["idx"], t["r_act"], t["g"], t["y"])
+        ibwd = lambda t: flop.flop_bwd_active_indexed(t["dy"], t["x"], t["Q"], t["Pt"], t["zc"], t["dzc"], t["idx"], t["r_act"],
+                                                      t["g"], t["dx"], t["dQ"], t["dPt"], t["da"], t["ws"])
+        t_idx = timeit(lambda: ([prep_i(t) for t in ls], [ifwd(t) for t in ls], [ibwd(t) for t in reversed(ls)]), iters)
+        emit(name, "active ranks read in place (P transposed): gate + index list + fwd + bwd", t_idx, 3 * fl_act, open_ranks=ra,
+             dense_equivalent_TFLOP_per_s=round(3 * fl / t_idx / 1e12, 1))
 
     # ---- C1: one fp32 layer ------------------------------------------------------
     if want("C1"):
