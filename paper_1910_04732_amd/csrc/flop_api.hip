@@ -286,17 +286,18 @@ inline int plan_ksplit(int64_t M, int64_t N, int64_t K)
 // first.  The model follows one compute unit: tiles are numbered by decreasing k extent (as the kernel numbers
 // them) and dealt to the 256 units in turn; a unit runs up to `occ` blocks at once; a block advances one 64-k
 // step (of each of its k groups) in max(lat_us, bytes staged per step by the unit's running blocks / intake rate)
-// and pays tile_us once for its first load and its output store.  The intake rate (100 KB/us per unit) and the
-// per-shape constants were fitted to per-launch times of the eight launches of the BERT-shaped step measured
-// with every shape forced in turn; what the model decides in practice: one round of large tiles beats two
+// and pays tile_us once for its first load and its output store.  The intake rate (130 KB/us per unit) and the
+// per-shape constants were fitted to per-launch times of the eight launches of the BERT-shaped step and the
+// sixteen of a 410-wide Transformer layer, measured with every shape forced in turn; what the model decides in
+// practice: one round of large tiles beats two
 // rounds of smaller ones, a product with few tiles and a long k extent wants small tiles or k groups, launches
 // of many rounds want the largest tile.
 struct ShapeModel { int cfg, bm, bn, groups, occ; double lat_us, tile_us; };
 constexpr ShapeModel kShapeModels[] = {
-    {2, 64, 64, 1, 3, 0.12, 0.5},   {9, 64, 96, 1, 2, 0.24, 2.5},   {4, 64, 96, 2, 1, 0.40, 3.5},
-    {1, 128, 64, 1, 2, 0.32, 1.5},  {0, 128, 128, 1, 2, 0.56, 4.0}, {7, 256, 128, 1, 1, 0.54, 5.5},
+    {2, 64, 64, 1, 3, 0.20, 2.0},   {9, 64, 96, 1, 2, 0.20, 3.0},   {3, 64, 64, 2, 1, 0.22, 2.5},  {4, 64, 96, 2, 1, 0.40, 3.0},
+    {1, 128, 64, 1, 2, 0.24, 3.0},  {0, 128, 128, 1, 2, 0.52, 4.5}, {7, 256, 128, 1, 1, 0.54, 4.5},
 };
-constexpr double kIntakeKBPerUs = 100.0;
+constexpr double kIntakeKBPerUs = 130.0;
 
 inline double model_launch_us(const ShapeModel& sm, const GemmDesc* d, const int* order, int count)
 {
@@ -371,6 +372,10 @@ inline int pick_cfg(const GemmDesc* d, int count, int xfer)
         n96 = n96 && d[i].N % 96 == 0;
     }
     const int64_t t256 = count_tiles(d, count, 256, 128);
+    // many rounds of long tiles: the launch runs at the chip's power limit, where the shape that moves the fewest
+    // bytes per flop wins (measured 3-6 % over 128x128 on 8192 x 3056 x 3056 .. 9168 products), whatever the
+    // model of a lightly loaded unit says
+    if (xfer == 16 && !narrow && t256 >= 768 && min_steps >= 32) return 7;
     int best = 2;
     double best_t = 0.0;
     bool first = true;
