@@ -136,7 +136,7 @@ def sweep() -> int:
     return 0
 
 
-def configs(only: str = "", no_cpu: bool = False) -> int:
+def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
     """Times every workload configuration (C1 .. C5) on the GPU, one JSON line per case.
 
     Shapes and gate statistics are those of the parity tests (paper_1910_04732_amd.synth); activations and
@@ -152,6 +152,9 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
     dev = torch.device("cuda:0")
     hc = flop.flop_hc(synth.BETA, synth.L, synth.R)
     gen = torch.Generator(device=dev).manual_seed(1910_04732)
+    if force_shape >= 0:   # measurement aid of include/flop_bench.h: one block shape for every bf16 transfer-kernel launch
+        flop.flop_bench_force_tile_shape(force_shape)
+        print(json.dumps({"note": "block shape forced: " + flop.flop_bench_tile_shapes()[force_shape]}), flush=True)
 
     def randn(rows, cols, var, dt, ld=None):
         buf = torch.zeros(rows, ld or cols, dtype=dt, device=dev)
@@ -162,7 +165,11 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
         return torch.empty(rows, ld or cols, dtype=dt, device=dev)[:, :cols]
 
     l0 = torch.empty(1, device=dev)
-    want = lambda key: not only or key in only.split(",")
+    keys = {k.split(":")[0]: k.endswith(":plain") for k in only.split(",") if k}
+    want = lambda key: not keys or key in keys
+    # "<key>:plain" (wide, C3): the rows-padded-to-128-bytes layout and the library's dense pass only, so that a
+    # profiler sees one workload per kernel name and grid size
+    plain = lambda key: keys.get(key, False)
 
     def cpu_line(config, case, fn, flops, sample, scale=1.0):
         """The fp64 oracle timed on the host cores beside the GPU lines of a configuration: a reported baseline,
@@ -357,11 +364,15 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
         # rows of 3056 / 9168 bfloat16 are not multiples of 128 bytes: a 64-k chunk of a row then straddles two cache
         # lines; both layouts are timed (the padded one has leading dimensions 3072 / 9216)
         for align, label in ((64, ", rows padded to 128 bytes"), (1, ", dense rows")):
+            if plain("wide") and align != 64:
+                continue
             big = [layer(8192, 3056, 3056, 9168, torch.bfloat16, la_big, u_big, align)]
             fl = lflops(big[0])
             name = "wide layer bf16 8192 x 3056 -> 9168, r=3056, half of the gates closed" + label
             emit(name, "gate + fwd + bwd", timeit(lambda: (gate(big[0]), fwd(big[0]), bwd(big[0])), 10), 3 * fl,
                  closed_fraction=round(float(big[0]["z"].eq(0).float().mean()), 3))
+            if plain("wide"):
+                continue
             active_rank_case(name, big, fl, 10)
             t = big[0]
             def vendor_big():
@@ -385,6 +396,8 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
     if want("C3"):
         for align, label in ((64, "rows padded to 128 bytes (448 / 1280 / 2112)"),
                              (8, "rows padded to 16 bytes (416 / 1232 / 2104)"), (1, "unpadded 410-wide rows")):
+            if plain("C3") and align != 64:
+                continue
             ms = []
             for m in range(4):
                 c = synth.config_c3(0, m)
@@ -393,14 +406,16 @@ def configs(only: str = "", no_cpu: bool = False) -> int:
             # 64 layer instances share the four matrices' buffers but own their workspace and gate gradient:
             # a pending gate gradient pins the workspace of its backward call until the shared finish
             inst = [dict(t, ws=torch.empty_like(t["ws"]), da=torch.empty_like(t["da"])) for _ in range(16) for t in reversed(ms)]
-            emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd, 64 matrices in sequence",
-                 timeit(lambda: [fwd(t) for _ in range(16) for t in ms], 5), fl)
+            if not plain("C3"):
+                emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd, 64 matrices in sequence",
+                     timeit(lambda: [fwd(t) for _ in range(16) for t in ms], 5), fl)
             emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd + bwd, 64 matrices in sequence",
                  timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all(inst)), 5),
                  3 * fl)
-            emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd + bwd, 64 matrices in sequence, HIP graph replay",
-                 timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all(inst)), 5,
-                        graph=True), 3 * fl)
+            if not plain("C3"):
+                emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd + bwd, 64 matrices in sequence, HIP graph replay",
+                     timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all(inst)), 5,
+                            graph=True), 3 * fl)
             del ms, inst
         c3 = [synth.config_c3(0, m) for m in range(4)]
         cpu_line("C3 bf16 16 x {QKV, out, FFN1, FFN2}", "gate + fwd + bwd + expected L0, 64 matrices",
@@ -519,7 +534,11 @@ def main() -> int:
     ap.add_argument("--trace-steps", type=int, default=20)
     ap.add_argument("--sweep", action="store_true", help="size sweep of the bandwidth-bound kernels instead of the step benchmark")
     ap.add_argument("--configs", action="store_true", help="time every workload configuration (C1..C5) instead of the step benchmark")
-    ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5")
+    ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain and "
+                                               "C3:plain run the 128-byte-padded layout and the dense pass only (for profiler runs)")
+    ap.add_argument("--force-shape", type=int, default=-1,
+                    help="with --configs: block shape number (see flop_bench_tile_shape_name) for every bf16 transfer-kernel "
+                         "launch instead of the library's choice; for profiler comparisons of shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -528,7 +547,7 @@ def main() -> int:
     if args.sweep:
         return sweep()
     if args.configs:
-        return configs(args.only, args.no_cpu_baseline)
+        return configs(args.only, args.no_cpu_baseline, args.force_shape)
 
     import numpy as np
     import torch

@@ -156,9 +156,10 @@ int launch_generic_groups(const GemmDesc* d, int count, hipStream_t stream)
 }
 
 // Generic kernel.  A launch of 64x64 tiles that leaves half of the compute units without a tile while every tile
-// has at least 8 steps runs with four k groups per block (1024 threads): such a launch lasts as long as one tile's
-// chain of load latencies and its own arithmetic on one unit, which the groups overlap; with a quarter of the
-// units busy or fewer the tiles shrink to 32x32 as well, each step's k split over a group's wavefronts.
+// has at least 8 steps lasts as long as one tile's chain of load latencies and its own arithmetic on one unit: it
+// runs on 32x32 tiles instead, in blocks of four k groups (1024 threads) with each step's k split over a group's
+// wavefronts (C1's products: 128 to 384 blocks instead of 32 to 96; 64x64 tiles with four k groups measured
+// 21 us per backward launch against 13).
 template <typename T, int B>
 int launch_generic(const GemmDesc* d, int count, hipStream_t stream)
 {
@@ -172,8 +173,7 @@ int launch_generic(const GemmDesc* d, int count, hipStream_t stream)
             fixed = fixed && !(d[i].seg || d[i].ext);
         }
         if (fixed && min_k != INT64_MAX && min_k >= 8 * BK) {
-            if (count_tiles(d, count, 64, 64) <= 64) return launch_generic_groups<T, 32, 4, 4>(d, count, stream);
-            if (count_tiles(d, count, 64, 64) <= 128) return launch_generic_groups<T, 64, 4>(d, count, stream);
+            if (count_tiles(d, count, 64, 64) <= 128) return launch_generic_groups<T, 32, 4, 4>(d, count, stream);
         }
     }
     return launch_generic_groups<T, B, 1>(d, count, stream);

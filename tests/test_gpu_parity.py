@@ -143,8 +143,8 @@ def test_layer_rows_padded_to_16_bytes(shape):
                          ids=lambda v: v if isinstance(v, str) else ("x".join(map(str, v)) if isinstance(v, tuple) else f"pad{v}"))
 def test_generic_kernel_k_groups(dtype, shape, pad):
     """Few tiles and long contractions on the register-staged kernel (float32; bfloat16 with odd leading
-    dimensions): blocks of four k groups on 64x64 tiles (65 to 128 tiles) and on 32x32 tiles whose k steps are
-    split over the wavefronts (up to 64 tiles of 64x64), with a ragged last round of the groups."""
+    dimensions): blocks of four k groups on 32x32 tiles whose k steps are split over the wavefronts (launches of up
+    to 128 tiles of 64x64), with a ragged last round of the groups."""
     n, d, r, dout = shape
     check_layer(synth.layer_inputs(5200 + n + d, n, d, r, dout, dtype), pad=pad)
 
