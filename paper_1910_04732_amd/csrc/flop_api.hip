@@ -355,6 +355,11 @@ inline int pick_cfg(const GemmDesc* d, int count, int xfer)
         const int64_t t128 = count_tiles(d, count, 128, 128);
         return (t128 >= 320 && !narrow) ? 0 : 2;
     }
+    // Extents that only the device knows (token segments of the embedding: the host sees upper bounds) defeat the
+    // model: large tiles when even the bounds give more than a round of them, else the smallest
+    bool segmented = false;
+    for (int i = 0; i < count; ++i) segmented = segmented || d[i].seg != nullptr;
+    if (segmented) return (count_tiles(d, count, 128, 128) >= 320 && !narrow) ? 0 : 2;
     int order[kMaxGroup];
     for (int i = 0; i < count; ++i) order[i] = i;
     for (int i = 1; i < count; ++i)
