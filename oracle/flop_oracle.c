@@ -17,7 +17,8 @@
  *   alpha[r], u[r], z[r]    one gate per rank-1 component, shared by the batch
  *   h = x Q^T   g = h .* z   y = g P^T
  *
- * Parity pins (tests marked "not gpu"): closed-form sampler points, Monte-Carlo
+ * Parity pins (tests marked "not gpu"): closed-form sampler points (train and
+ * deterministic mode, value and slope), noise at the ends of its range, Monte-Carlo
  * agreement of the sampler with Eq.(3), all-gates-open == dense product via a
  * library matmul, closing a gate == deleting the component, finite differences
  * for every gradient, brute-force compaction, one-hot embedding equivalence.
