@@ -258,6 +258,18 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
     def bwd_all(ts):   # backward of several layers, the last stage of their gate gradients in shared launches
         flop.flop_gate_grad_finish([flop.flop_bwd_deferred(t["dy"], t["x"], t["Q"], t["P"], t["z"], t["dzda"], t["g"],
                                                            t["dx"], t["dQ"], t["dP"], t["da"], t["ws"]) for t in ts])
+    def bwd_all_deferred(ts, per_call=4):
+        """Backward of several layers with dP and dQ left out of every call and computed afterwards, `per_call`
+        layers (2 x per_call products) to a flop_weight_grad_finish call."""
+        gate_items, weight_items = [], []
+        for t in ts:
+            gi, wi = flop.flop_bwd_defer_weights(t["dy"], t["x"], t["Q"], t["P"], t["z"], t["dzda"], t["g"],
+                                                 t["dx"], t["dQ"], t["dP"], t["da"], t["ws"])
+            gate_items.append(gi)
+            weight_items.append(wi)
+        for i in range(0, len(weight_items), per_call):
+            flop.flop_weight_grad_finish(weight_items[i:i + per_call])
+        flop.flop_gate_grad_finish(gate_items)
     gate = lambda t: flop.flop_gate_sample(t["la"], t["u"], hc, flop.FLOP_GATE_TRAIN, t["z"], t["dzda"])
     lflops = lambda t: 2.0 * t["n"] * t["r"] * (t["d"] + t["dout"])
 
@@ -414,6 +426,12 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
             emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd + bwd, 64 matrices in sequence",
                  timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all(inst)), 5),
                  3 * fl)
+            # the same pass with the weight gradients of each layer's four matrices in one launch of eight products
+            # behind that layer's backward calls (every instance then needs operands of its own to stay alive; the
+            # shared buffers here only serve the timing)
+            emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label,
+                 "fwd + bwd, 64 matrices in sequence, weight gradients deferred (one launch per layer of four matrices)",
+                 timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all_deferred(inst)), 5), 3 * fl)
             if not plain("C3"):
                 emit("C3 bf16 16 x {QKV, out, FFN1, FFN2}, " + label, "fwd + bwd, 64 matrices in sequence, HIP graph replay",
                      timeit(lambda: ([fwd(t) for _ in range(16) for t in ms], bwd_all(inst)), 5,

@@ -188,6 +188,50 @@ int flop_bwd_deferred(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t do
 int flop_gate_grad_finish(const flop_gate_grad_pending* items, int32_t count, void* stream);
 
 /*
+ * flop_bwd_deferred with the weight gradients left for later as well.  Section 3's gradients dP = dy^T g and
+ * dQ = dh^T x (dh = (dy P) .* z) feed only the optimiser's update of the step, not the rest of the backward pass; their
+ * contraction runs over the n tokens, far longer than those of dh and dx on narrow layers, and a launch lasts as
+ * long as its longest tile.  This call computes dx and the column sums of the gate gradient and writes to
+ * *weights (host memory) the operands of the two products it left out: dy, g_saved, x, the gated dh inside
+ * `workspace`, and the destinations dP, dQ (either may be NULL: that product is then not wanted).
+ * flop_weight_grad_finish later computes them for many layers in shared launches of up to eight products.
+ * Until that call has been made on the same stream, dy, x, g_saved and the workspace must stay untouched
+ * (the workspace also holds the pending gate-gradient sums, as for flop_bwd_deferred).
+ * dlog_alpha may be NULL here (then *pending is left untouched and may be NULL).
+ */
+typedef struct {
+    int32_t dtype;             /* flop_dtype of the layer */
+    int64_t n, d, r, dout;
+    const void* dy; int64_t lddy;      /* device, n x dout */
+    const void* g; int64_t ldg;        /* device, n x r: g_saved */
+    const void* dh; int64_t ldh;       /* device, inside the call's workspace: (dy P) .* z, n x r; NULL if dQ is */
+    const void* x; int64_t ldx;        /* device, n x d */
+    void* dP; int64_t lddp;            /* device, dout x r, or NULL */
+    void* dQ; int64_t lddq;            /* device, r x d, or NULL */
+    void* split_ws; size_t split_bytes; /* device, inside the call's workspace: scratch for a product cut along k */
+} flop_weight_grad_pending;
+
+int flop_bwd_defer_weights(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                           const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                           const void* Q, int64_t ldq, const void* P, int64_t ldp,
+                           const float* z, const float* dzda, const void* g_saved, int64_t ldg,
+                           void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
+                           float* dlog_alpha, int accumulate,
+                           void* workspace, size_t workspace_bytes, void* stream,
+                           flop_gate_grad_pending* pending, flop_weight_grad_pending* weights);
+
+/*
+ * dP = dy^T g and dQ = dh^T x (Section 3) for `count` pending layers (host array), up to eight products to a
+ * launch.  Products that the bfloat16 transfer kernel can take unsplit (16-byte aligned rows, operands within
+ * 2 GiB) and all float32 products are grouped in the order given; any other layer's pair is launched on its own
+ * with the k-split scratch of its workspace.  Results agree with flop_bwd's to float32 summation order (a
+ * different block shape may add the k steps in two interleaved halves); every run of this call on the same
+ * items gives the same bits.  FLOP_ERR_NULL / FLOP_ERR_SHAPE / FLOP_ERR_STRIDE / FLOP_ERR_DTYPE for malformed
+ * items (nothing is launched then).
+ */
+int flop_weight_grad_finish(const flop_weight_grad_pending* items, int32_t count, void* stream);
+
+/*
  * The two small launches at the boundary between two training steps in one: flop_gate_grad_finish for the
  * step that ends (items, count) and flop_gate_sample_l0 for the step that begins (every other argument, as
  * there).  With count <= 16 and n_gates <= 4096 this is a single launch; otherwise the two calls are made one

@@ -401,7 +401,9 @@ __device__ __forceinline__ void embed_sort_body(
 // Keys: id and token position packed so that equal ids keep token order.  KeyT = 64 bits:
 // id << 32 | token.  KeyT = 32 bits, when (largest id - id_base) and the token positions fit
 // together: (id - id_base) << tok_bits | token, sorted by a stable radix sort on the id field.
-template <typename KeyT>
+// KPT = n_pow2 / kSortThreads keys per thread (1, 2, 4, 8 or 16): a kernel per value, so that the registers of a
+// small batch are not those of the largest.
+template <typename KeyT, int KPT>
 __global__ __launch_bounds__(kSortThreads) void embed_sort_kernel(
     const int64_t* __restrict__ ids, int n, int n_pow2, EmbedClusterArgs cl, int64_t id_base, int tok_bits, int radix_passes,
     int32_t* __restrict__ perm, int32_t* __restrict__ rows, int32_t* __restrict__ seg,
@@ -415,17 +417,8 @@ __global__ __launch_bounds__(kSortThreads) void embed_sort_kernel(
     __syncthreads();
     KeyT* key = (KeyT*)smem_raw;
     unsigned char* after_keys = smem_raw + (size_t)n_pow2 * sizeof(KeyT);
-#define FLOP_SORT_BODY(KPT)                                                                                             \
-    embed_sort_body<KPT, KeyT>(ids, n, n_pow2, cl, id_base, tok_bits, radix_passes, perm, rows, seg, run_start,   \
-                               uniq_ids, run_id, key, after_keys, sh)
-    switch (n_pow2 / kSortThreads) {
-        case 1: FLOP_SORT_BODY(1); break;
-        case 2: FLOP_SORT_BODY(2); break;
-        case 4: FLOP_SORT_BODY(4); break;
-        case 8: FLOP_SORT_BODY(8); break;
-        default: FLOP_SORT_BODY(16); break;
-    }
-#undef FLOP_SORT_BODY
+    embed_sort_body<KPT, KeyT>(ids, n, n_pow2, cl, id_base, tok_bits, radix_passes, perm, rows, seg, run_start,
+                               uniq_ids, run_id, key, after_keys, sh);
 }
 
 // g_c[i - first_c, :] = round(E_c[rows[i], :] .* z_c), one block per sorted position.

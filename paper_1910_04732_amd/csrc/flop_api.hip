@@ -60,6 +60,9 @@ struct GemmDesc {
     const float* gate_alpha; const float* gate_u; float gate_beta, gate_l, gate_r;
     // B gathered by an index list (see GemmProblem): rows of the b_map_rows-row matrix at B
     const int32_t* b_map; int64_t b_map_rows;
+    // launch-wide (read from the first product): lay the products out over the XCDs one after another instead
+    // of cutting every product into eight (see GemmGroup::contiguous); needs host-known extents and no k split
+    bool few_xcds;
 };
 
 // Kernels that need more dynamic LDS than the default limit get the attribute once per device (a function's
@@ -131,6 +134,41 @@ int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, in
     grp.count = count;
     if (tiles == 0) return FLOP_OK;
     grp.tile_blocks = 8 * per_xcd_total;
+    bool contiguous = count > 0 && d[0].few_xcds;
+    for (int i = 0; i < count; ++i) contiguous = contiguous && !d[i].seg && !d[i].ext && d[i].ksplit <= 1;
+    if (contiguous) {
+        // Cut the sequence of all tiles (products in launch order) into eight pieces of equal work; a tile's work is
+        // its 64-k steps plus what its first load and its store cost in steps.
+        constexpr double kTileOverheadSteps = 8.0;
+        double work[kMaxGroup], total = 0.0;
+        int begin[kMaxGroup + 1];
+        begin[0] = 0;
+        for (int i = 0; i < count; ++i) {
+            const int t = grp.p[i].tiles_m * grp.p[i].tiles_n;
+            work[i] = (double)((d[i].K + 63) / 64) + kTileOverheadSteps;
+            total += work[i] * t;
+            begin[i + 1] = begin[i] + t;
+            grp.p[i].xcd_begin = begin[i];
+        }
+        grp.contiguous = 1;
+        grp.xcd_first[0] = 0;
+        int longest = 0;
+        for (int x = 1; x <= 8; ++x) {
+            const double target = total * x / 8.0;
+            double cum = 0.0;
+            int pos = begin[count];
+            for (int i = 0; i < count; ++i) {
+                const double w = work[i] * (begin[i + 1] - begin[i]);
+                if (cum + w >= target) { pos = begin[i] + (int)((target - cum) / work[i] + 0.5); break; }
+                cum += w;
+            }
+            if (x == 8 || pos > begin[count]) pos = begin[count];
+            if (pos < grp.xcd_first[x - 1]) pos = grp.xcd_first[x - 1];
+            grp.xcd_first[x] = pos;
+            longest = pos - grp.xcd_first[x - 1] > longest ? pos - grp.xcd_first[x - 1] : longest;
+        }
+        grp.tile_blocks = 8 * longest;
+    }
     if (rider) {   // extra blocks behind the tiles do the step-boundary work
         grp.rider = *rider;
         grp.rider_blocks = rider->bx * (rider->count + 1);
@@ -511,7 +549,8 @@ int launch_group(flop_dtype dt, const GemmDesc* d_in, int count, hipStream_t str
     if (dt == FLOP_BF16) {
         // the DMA kernel fixes the layout of B per launch; A may differ between the products
         int xfer = 16;
-        int min_split[kMaxGroup] = {1, 1, 1, 1};
+        int min_split[kMaxGroup];
+        for (int i = 0; i < kMaxGroup; ++i) min_split[i] = 1;
         for (int i = 0; i < count; ++i) {
             const int w = d[i].b_kmajor == d[0].b_kmajor ? dma_width(d[i], &min_split[i]) : 0;
             xfer = w < xfer ? w : xfer;
@@ -809,7 +848,7 @@ int bwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
              void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
              float* dlog_alpha, int accumulate,
              void* workspace, size_t workspace_bytes, void* stream, flop_gate_grad_pending* pending = nullptr,
-             const flop_boundary_job* boundary = nullptr)
+             const flop_boundary_job* boundary = nullptr, flop_weight_grad_pending* weights = nullptr)
 {
     if (!valid_dtype(dt)) return FLOP_ERR_DTYPE;
     if (n < 0 || d <= 0 || r <= 0 || dout <= 0) return FLOP_ERR_SHAPE;
@@ -833,6 +872,12 @@ int bwd_impl(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
     const size_t split_bytes = bwd_split_bytes(n, d, r, dout);
     const bool need_dh = dx || dQ || dlog_alpha;
     int rc;
+    if (weights) {   // dP and dQ are left to flop_weight_grad_finish: this call only records their operands
+        *weights = {(int32_t)dt, n, d, r, dout, dy, lddy, g_saved, ldg, dQ ? dh : nullptr, ldh, x, ldx, dP, lddp, dQ, lddq,
+                    split_ws, split_bytes};
+        dP = nullptr;
+        dQ = nullptr;
+    }
 
     // Phase 1: dh = (dy P) .* z and dP = dy^T g.
     GemmDesc ph1[2];
@@ -1121,6 +1166,86 @@ int flop_bwd_deferred(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t do
     if (!pending) return FLOP_ERR_NULL;
     return bwd_impl(dt, n, d, r, dout, dy, lddy, x, ldx, Q, ldq, P, ldp, z, dzda, nullptr, g_saved, ldg, dx, lddx,
                     dQ, lddq, dP, lddp, dlog_alpha, accumulate, workspace, workspace_bytes, stream, pending);
+}
+
+int flop_bwd_defer_weights(flop_dtype dt, int64_t n, int64_t d, int64_t r, int64_t dout,
+                           const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                           const void* Q, int64_t ldq, const void* P, int64_t ldp,
+                           const float* z, const float* dzda, const void* g_saved, int64_t ldg,
+                           void* dx, int64_t lddx, void* dQ, int64_t lddq, void* dP, int64_t lddp,
+                           float* dlog_alpha, int accumulate,
+                           void* workspace, size_t workspace_bytes, void* stream,
+                           flop_gate_grad_pending* pending, flop_weight_grad_pending* weights)
+{
+    if (!weights || (dlog_alpha && !pending)) return FLOP_ERR_NULL;
+    return bwd_impl(dt, n, d, r, dout, dy, lddy, x, ldx, Q, ldq, P, ldp, z, dzda, nullptr, g_saved, ldg, dx, lddx,
+                    dQ, lddq, dP, lddp, dlog_alpha, accumulate, workspace, workspace_bytes, stream,
+                    dlog_alpha ? pending : nullptr, nullptr, weights);
+}
+
+int flop_weight_grad_finish(const flop_weight_grad_pending* items, int32_t count, void* stream)
+{
+    if (count < 0) return FLOP_ERR_SHAPE;
+    if (count == 0) return FLOP_OK;
+    if (!items) return FLOP_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const flop_weight_grad_pending& it = items[i];
+        if (!valid_dtype(it.dtype)) return FLOP_ERR_DTYPE;
+        if (it.n < 0 || it.d <= 0 || it.r <= 0 || it.dout <= 0) return FLOP_ERR_SHAPE;
+        if (it.n > kMaxDim || it.d > kMaxDim || it.r > kMaxDim || it.dout > kMaxDim) return FLOP_ERR_SHAPE;
+        if (it.dP && it.n > 0 && (!it.dy || !it.g)) return FLOP_ERR_NULL;
+        if (it.dQ && it.n > 0 && (!it.dh || !it.x)) return FLOP_ERR_NULL;
+        if (it.dP && (it.lddy < it.dout || it.ldg < it.r || it.lddp < it.r)) return FLOP_ERR_STRIDE;
+        if (it.dQ && (it.ldh < it.r || it.ldx < it.d || it.lddq < it.d)) return FLOP_ERR_STRIDE;
+        if (ld_too_large({it.lddy, it.ldg, it.ldh, it.ldx, it.lddp, it.lddq})) return FLOP_ERR_STRIDE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // Class of a product for sharing a launch: 0 = none (launched with its layer only), 1 = float32 (generic
+    // kernel), 16 / 4 = bfloat16 on the transfer kernel, unsplit, with transfers of that many bytes.  A launch
+    // runs at the narrowest width of its members, so the classes are kept apart.
+    auto share_class = [](flop_dtype dt, const GemmDesc& g) {
+        if (g.K <= 0) return 0;
+        if (dt != FLOP_BF16) return 1;
+        int min_split = 1;
+        const int w = dma_width(g, &min_split);
+        return min_split == 1 ? w : 0;
+    };
+    GemmDesc batch[kMaxGroup];
+    int nb = 0, batch_layers = 0, batch_dt = FLOP_BF16, batch_cls = 0;
+    const flop_weight_grad_pending* batch_first = nullptr;
+    int rc = FLOP_OK;
+    auto flush = [&]() {
+        if (nb == 0) return (int)FLOP_OK;
+        // a launch that serves a single layer may cut its products along k into that layer's scratch
+        const bool one = batch_layers == 1;
+        const int rcl = launch_group((flop_dtype)batch_dt, batch, nb, st, nullptr, one ? batch_first->split_ws : nullptr,
+                                     one ? batch_first->split_bytes : 0);
+        nb = 0;
+        batch_layers = 0;
+        return rcl;
+    };
+    for (int i = 0; i < count; ++i) {
+        const flop_weight_grad_pending& it = items[i];
+        GemmDesc pr[2];
+        int c = 0;
+        if (it.dP) pr[c++] = {it.dy, it.lddy, false, it.g, it.ldg, false, it.dP, it.lddp, it.dout, it.r, it.n, nullptr};
+        if (it.dQ) pr[c++] = {it.dh, it.ldh, false, it.x, it.ldx, false, it.dQ, it.lddq, it.r, it.d, it.n, nullptr};
+        if (c == 0) continue;
+        int cls = share_class((flop_dtype)it.dtype, pr[0]);
+        if (c == 2) { const int c1 = share_class((flop_dtype)it.dtype, pr[1]); cls = c1 < cls ? c1 : cls; }
+        if (cls == 0) {   // on its own, with everything launch_group can fall back to
+            if ((rc = flush()) != FLOP_OK) return rc;
+            rc = launch_group((flop_dtype)it.dtype, pr, c, st, nullptr, it.split_ws, it.split_bytes);
+            if (rc != FLOP_OK) return rc;
+            continue;
+        }
+        if (nb + c > kMaxGroup || (nb && (batch_dt != it.dtype || batch_cls != cls)))
+            if ((rc = flush()) != FLOP_OK) return rc;
+        if (nb == 0) { batch_first = &it; batch_dt = it.dtype; batch_cls = cls; }
+        for (int q = 0; q < c; ++q) { batch[nb] = pr[q]; batch[nb++].few_xcds = true; }
+        ++batch_layers;
+    }
+    return flush();
 }
 
 int flop_gate_grad_finish(const flop_gate_grad_pending* items, int32_t count, void* stream)
@@ -1569,25 +1694,35 @@ int flop_embed_fwd(flop_dtype dt, int64_t n_tokens, const int64_t* ids, int32_t 
     int radix_passes = 1;
     while (radix_passes < 8 && ((1ull << (kRadixBits * radix_passes)) - 1) <= span) ++radix_passes;
     const size_t radix_lds = (size_t)kRadixBuckets * kSortThreads * sizeof(uint16_t);
-    static AttrOnce sort_attr;
-    int sort_dev = 0;
-    if (sort_attr.needed(&sort_dev)) {
-        if (hipFuncSetAttribute((const void*)embed_sort_kernel<unsigned long long>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kEmbedMaxTokens * 8) != hipSuccess ||
-            hipFuncSetAttribute((const void*)embed_sort_kernel<unsigned>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kEmbedMaxTokens * 4 + radix_lds)) != hipSuccess)
-            return FLOP_ERR_HIP;
-        sort_attr.done(sort_dev);
-    }
-    if (narrow)
-        hipLaunchKernelGGL(embed_sort_kernel<unsigned>, dim3(1), dim3(kSortThreads), (size_t)n_pow2 * 4 + radix_lds, st, ids,
-                           (int)n_tokens, n_pow2, ca, id_base, tok_bits, radix_passes, perm, rows, seg,
+    auto sort_launch = [&](auto key_tag, auto kpt_tag) -> int {
+        using KeyT = decltype(key_tag);
+        constexpr int KPT = decltype(kpt_tag)::value;
+        static AttrOnce attr;   // one per instantiation of this lambda's call operator
+        int sort_dev = 0;
+        const size_t lds = (size_t)n_pow2 * sizeof(KeyT) + (sizeof(KeyT) == 4 ? radix_lds : 0);
+        if (attr.needed(&sort_dev)) {
+            const size_t most = (size_t)kSortThreads * KPT * sizeof(KeyT) + (sizeof(KeyT) == 4 ? radix_lds : 0);
+            if (hipFuncSetAttribute((const void*)embed_sort_kernel<KeyT, KPT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)most) != hipSuccess)
+                return FLOP_ERR_HIP;
+            attr.done(sort_dev);
+        }
+        hipLaunchKernelGGL((embed_sort_kernel<KeyT, KPT>), dim3(1), dim3(kSortThreads), lds, st, ids, (int)n_tokens, n_pow2, ca,
+                           id_base, tok_bits, sizeof(KeyT) == 4 ? radix_passes : 0, perm, rows, seg,
                            (int32_t*)(sv + L.run_start), (int64_t*)(sv + L.uniq_ids), (int32_t*)(sv + L.run_id));
-    else
-        hipLaunchKernelGGL(embed_sort_kernel<unsigned long long>, dim3(1), dim3(kSortThreads), (size_t)n_pow2 * 8, st, ids,
-                           (int)n_tokens, n_pow2, ca, id_base, tok_bits, 0, perm, rows, seg,
-                           (int32_t*)(sv + L.run_start), (int64_t*)(sv + L.uniq_ids), (int32_t*)(sv + L.run_id));
-    if (hipGetLastError() != hipSuccess) return FLOP_ERR_HIP;
+        return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
+    };
+    auto sort_keys = [&](auto key_tag) -> int {
+        switch (n_pow2 / kSortThreads) {
+            case 1: return sort_launch(key_tag, std::integral_constant<int, 1>());
+            case 2: return sort_launch(key_tag, std::integral_constant<int, 2>());
+            case 4: return sort_launch(key_tag, std::integral_constant<int, 4>());
+            case 8: return sort_launch(key_tag, std::integral_constant<int, 8>());
+            default: return sort_launch(key_tag, std::integral_constant<int, 16>());
+        }
+    };
+    rc = narrow ? sort_keys((unsigned)0) : sort_keys((unsigned long long)0);
+    if (rc != FLOP_OK) return rc;
     if (dt == FLOP_BF16)
         hipLaunchKernelGGL(embed_gather_gate_kernel<2>, dim3((unsigned)n_tokens), dim3(128), 0, st, ca, rows, seg);
     else

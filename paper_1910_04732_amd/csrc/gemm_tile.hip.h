@@ -1,6 +1,6 @@
 // Grouped MFMA tile kernel for the contractions of the gated factorized layer.
 //
-// One launch executes up to four independent products C = op(A) op(B) whose
+// One launch executes up to eight independent products C = op(A) op(B) whose
 // output tiles are laid end to end in the grid, so that small products (the
 // shapes of Section 4.1 are a few GFLOP each) still fill 256 compute units.
 // Each operand is described by its own layout flag, which covers the three
@@ -29,7 +29,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kGemmThreads = 256;
-constexpr int kMaxGroup = 4;
+constexpr int kMaxGroup = 8;
 constexpr int kTileBand = 8;   // tile rows per band of the tile numbering (see locate_tile)
 constexpr int kStepBytes = 128;            // bytes of k staged per main-loop step
 constexpr int kLdsRow = kStepBytes + 16;   // padded LDS row
@@ -86,7 +86,23 @@ struct GemmGroup {
     // the launch do the step-boundary work instead of a tile.
     int tile_blocks, rider_blocks;
     BoundaryRider rider;
+    // Alternative block -> tile mapping for launches of several products with host-known extents (see locate_tile):
+    // the products' tiles form one sequence, product after product, and XCD x works on its tiles
+    // xcd_first[x] .. xcd_first[x + 1] - 1; p[q].xcd_begin is then product q's first position in that sequence.
+    int contiguous;
+    int xcd_first[9];
 };
+
+// Tiles are numbered band by band: a band is kTileBand tile rows, walked column by
+// column, so that the tiles in flight on an XCD share few row and column panels.
+__device__ __forceinline__ void decode_tile(const GemmProblem& pr, int t, int& tile_m, int& tile_n)
+{
+    const int band_tiles = kTileBand * pr.tiles_n;
+    const int band = t / band_tiles, in_band = t - band * band_tiles;
+    const int rows_here = min(kTileBand, pr.tiles_m - band * kTileBand);
+    tile_n = in_band / rows_here;
+    tile_m = band * kTileBand + (in_band - tile_n * rows_here);
+}
 
 // Block -> (problem, tile).  Hardware hands consecutive block ids to the eight
 // XCDs in turn, each with its own L2.  Every problem's tile list is cut into
@@ -99,10 +115,23 @@ template <int ES, int BM, int BN>
 __device__ __forceinline__ bool locate_tile(const GemmGroup& grp, GemmProblem& pr, int& tile_m, int& tile_n)
 {
     const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
-    pr = grp.p[0];
+    if (grp.contiguous) {
+        // One sequence of tiles cut into eight contiguous pieces of equal work: a product lies on as few XCDs as
+        // its size allows, so that its operand panels are fetched into few L2s (weight-gradient products of many
+        // layers in one launch: every operand is as long as the token count and used by one product only).
+        const int pos = grp.xcd_first[xcd] + i;
+        if (pos >= grp.xcd_first[xcd + 1]) return false;
+        int q = 0;
 #pragma unroll
-    for (int q = 1; q < kMaxGroup; ++q)
-        if (q < grp.count && i >= grp.p[q].xcd_begin) pr = grp.p[q];
+        for (int j = 1; j < kMaxGroup; ++j) q += (j < grp.count && pos >= grp.p[j].xcd_begin) ? 1 : 0;
+        pr = grp.p[q];
+        decode_tile(pr, pos - pr.xcd_begin, tile_m, tile_n);
+        return true;
+    }
+    int q = 0;   // xcd_begin ascends: the problem's index is the number of later problems that start at or before i
+#pragma unroll
+    for (int j = 1; j < kMaxGroup; ++j) q += (j < grp.count && i >= grp.p[j].xcd_begin) ? 1 : 0;
+    pr = grp.p[q];
     // Extents known only on the device shrink the problem first, so that the tiles that remain
     // are again spread evenly over the XCDs (the grid was sized for the host's upper bounds).
     if (pr.seg) {
@@ -141,13 +170,7 @@ __device__ __forceinline__ bool locate_tile(const GemmGroup& grp, GemmProblem& p
         pr.K = k_here;
         pr.split_out += (int64_t)slice * pr.M * pr.N;
     }
-    // Tiles are numbered band by band: a band is kTileBand tile rows, walked column by
-    // column, so that the tiles in flight on an XCD share few row and column panels.
-    const int band_tiles = kTileBand * pr.tiles_n;
-    const int band = t / band_tiles, in_band = t - band * band_tiles;
-    const int rows_here = min(kTileBand, pr.tiles_m - band * kTileBand);
-    tile_n = in_band / rows_here;
-    tile_m = band * kTileBand + (in_band - tile_n * rows_here);
+    decode_tile(pr, t, tile_m, tile_n);
     return true;
 }
 

@@ -47,6 +47,15 @@ class flop_gate_grad_pending(ctypes.Structure):
                 ("chunks", ctypes.c_int32), ("accumulate", ctypes.c_int32)]
 
 
+class flop_weight_grad_pending(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n", ctypes.c_int64), ("d", ctypes.c_int64), ("r", ctypes.c_int64),
+                ("dout", ctypes.c_int64),
+                ("dy", ctypes.c_void_p), ("lddy", ctypes.c_int64), ("g", ctypes.c_void_p), ("ldg", ctypes.c_int64),
+                ("dh", ctypes.c_void_p), ("ldh", ctypes.c_int64), ("x", ctypes.c_void_p), ("ldx", ctypes.c_int64),
+                ("dP", ctypes.c_void_p), ("lddp", ctypes.c_int64), ("dQ", ctypes.c_void_p), ("lddq", ctypes.c_int64),
+                ("split_ws", ctypes.c_void_p), ("split_bytes", ctypes.c_size_t)]
+
+
 class flop_boundary_job(ctypes.Structure):
     _fields_ = [("items", ctypes.POINTER(flop_gate_grad_pending)), ("count", ctypes.c_int32),
                 ("log_alpha", ctypes.c_void_p), ("u", ctypes.c_void_p), ("n_gates", ctypes.c_int64), ("hc", flop_hc),
@@ -88,6 +97,9 @@ def lib():
         L.flop_fwd_sampling.argtypes = ([_int] + [_i64] * 4 + [_vp, _i64] * 3 + [ctypes.POINTER(flop_boundary_job), _i64]
                                         + [_vp, _i64, _vp, _i64, _vp, _sz, _vp])
         L.flop_gate_grad_finish.argtypes = [ctypes.POINTER(flop_gate_grad_pending), ctypes.c_int32, _vp]
+        L.flop_bwd_defer_weights.argtypes = L.flop_bwd.argtypes + [ctypes.POINTER(flop_gate_grad_pending),
+                                                                   ctypes.POINTER(flop_weight_grad_pending)]
+        L.flop_weight_grad_finish.argtypes = [ctypes.POINTER(flop_weight_grad_pending), ctypes.c_int32, _vp]
         L.flop_mfma_probe.argtypes = [ctypes.c_int, _i64, ctypes.c_int32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
         L.flop_step_boundary.argtypes = [ctypes.POINTER(flop_gate_grad_pending), ctypes.c_int32, _vp, _vp, _i64, flop_hc,
                                          _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -275,6 +287,39 @@ def flop_bwd_deferred(dy, x, Q, P, z, dzda, g_saved, dx, dQ, dP, dlog_alpha, ws,
                                    _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream), ctypes.byref(pending)),
            "flop_bwd_deferred")
     return pending
+
+
+def flop_bwd_defer_weights(dy, x, Q, P, z, dzda, g_saved, dx, dQ, dP, dlog_alpha, ws, accumulate=False, stream=None):
+    """flop_bwd_deferred that also leaves dP and dQ for later; returns (pending gate gradient or None, pending
+    weight gradients) for flop_gate_grad_finish / flop_weight_grad_finish.  ``dy``, ``x``, ``g_saved`` and ``ws`` must
+    stay alive and untouched until those calls."""
+    dt = _dt(x)
+    n, d = x.shape
+    r, dout = Q.shape[0], P.shape[0]
+    assert dy.shape == (n, dout) and Q.shape == (r, d) and P.shape == (dout, r) and g_saved.shape == (n, r)
+    dyp, lddy = _mat(dy, "dy")
+    xp, ldx = _mat(x, "x")
+    qp, ldq = _mat(Q, "Q")
+    pp, ldp = _mat(P, "P")
+    gp, ldg = _mat(g_saved, "g_saved")
+    dxp, lddx = (None, 0) if dx is None else _mat(dx, "dx")
+    dqp, lddq = (None, 0) if dQ is None else _mat(dQ, "dQ")
+    dpp, lddp = (None, 0) if dP is None else _mat(dP, "dP")
+    pending = flop_gate_grad_pending()
+    weights = flop_weight_grad_pending()
+    _check(lib().flop_bwd_defer_weights(dt, n, d, r, dout, dyp, lddy, xp, ldx, qp, ldq, pp, ldp,
+                                        _vec(z, "z"), _vec(dzda, "dzda"), gp, ldg, dxp, lddx, dqp, lddq, dpp, lddp,
+                                        _vec(dlog_alpha, "dlog_alpha"), 1 if accumulate else 0,
+                                        _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream),
+                                        ctypes.byref(pending), ctypes.byref(weights)),
+           "flop_bwd_defer_weights")
+    return (None if dlog_alpha is None else pending), weights
+
+
+def flop_weight_grad_finish(items, stream=None):
+    """dP and dQ of the given pending items (from flop_bwd_defer_weights), up to eight products to a launch."""
+    arr = (flop_weight_grad_pending * max(len(items), 1))(*items)
+    _check(lib().flop_weight_grad_finish(arr, len(items), _stream(stream)), "flop_weight_grad_finish")
 
 
 def flop_fwd_sampling(x, Q, P, log_alpha, u, hc: flop_hc, z, dzda, l0_sum, gate_offset, g_saved, y, w=None, l0_grad=None,

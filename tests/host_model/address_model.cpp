@@ -164,6 +164,26 @@ void indexed_pass(flop_dtype dt, std::vector<Layer>& layers)
     }
 }
 
+// Weight gradients left out of every layer's backward call and computed afterwards in shared launches
+// (flop_bwd_defer_weights / flop_weight_grad_finish): up to eight products of different layers in one grid.
+void deferred_weights_pass(flop_dtype dt, std::vector<Layer>& layers)
+{
+    std::vector<flop_gate_grad_pending> gate_items(layers.size());
+    std::vector<flop_weight_grad_pending> weight_items(layers.size());
+    for (size_t i = 0; i < layers.size(); ++i) {
+        Layer& t = layers[i];
+        Buf z = gates(t.r, 0.5f), dz = gates(t.r, 0.1f);
+        must(flop_bwd_defer_weights(dt, t.n, t.d, t.r, t.dout, t.dy.p, t.dout, t.x.p, t.d, t.Q.p, t.d, t.P.p, t.r, z.f(), dz.f(),
+                                    t.g.p, t.r, t.dx.p, t.d, i % 3 == 2 ? nullptr : t.dQ.p, t.d, t.dP.p, t.r, t.da.f(), 0,
+                                    t.ws.p, t.ws.bytes, nullptr, &gate_items[i], &weight_items[i]), "flop_bwd_defer_weights");
+    }
+    // the same list twice over, so that a single layer also meets launches shared with copies of itself
+    std::vector<flop_weight_grad_pending> twice(weight_items);
+    twice.insert(twice.end(), weight_items.begin(), weight_items.end());
+    must(flop_weight_grad_finish(twice.data(), (int32_t)twice.size(), nullptr), "flop_weight_grad_finish");
+    must(flop_weight_grad_finish(weight_items.data(), 1, nullptr), "flop_weight_grad_finish (one layer)");
+}
+
 void run_case(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, int64_t extra, bool next_gates)
 {
     std::vector<Layer> layers;
@@ -174,6 +194,7 @@ void run_case(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, 
     plain_pass(dt, layers, G, la.f(), u.f(), w.f());
     riding_pass(dt, layers, G, la.f(), u.f(), w.f(), next_gates);
     indexed_pass(dt, layers);
+    deferred_weights_pass(dt, layers);
 }
 
 std::string describe(flop_dtype dt, const std::vector<std::array<int64_t, 4>>& shapes, int64_t extra, bool next_gates)

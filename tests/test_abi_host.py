@@ -59,6 +59,32 @@ def test_oversized_leading_dimensions_are_rejected(lib):
                                      p, big, p, 4, p, 4, p, 0, p, 1 << 20, None) == -3
 
 
+def test_pending_weight_gradients_are_validated_before_any_launch(lib):
+    """flop_weight_grad_finish checks every item first; a malformed one anywhere in the list rejects the call."""
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p).value
+    W = flop.flop_weight_grad_pending
+
+    def item(**kw):
+        f = dict(dtype=flop.FLOP_BF16, n=2, d=4, r=4, dout=4, dy=p, lddy=4, g=p, ldg=4, dh=p, ldh=4, x=p, ldx=4,
+                 dP=p, lddp=4, dQ=p, lddq=4, split_ws=None, split_bytes=0)
+        f.update(kw)
+        return W(**f)
+    L = lib
+    for bad, status in ((item(dtype=9), -4), (item(n=-1), -2), (item(dout=0), -2), (item(lddy=3), -3), (item(ldh=3), -3),
+                        (item(lddq=(1 << 32) + 4), -3), (item(g=None), -1), (item(x=None), -1)):
+        arr = (W * 2)(item(dP=None, dQ=None), bad)
+        assert L.flop_weight_grad_finish(arr, 2, None) == status
+    assert L.flop_weight_grad_finish(None, 0, None) == 0
+    assert L.flop_weight_grad_finish(None, 3, None) == -1
+    assert L.flop_weight_grad_finish((W * 1)(item()), -1, None) == -2
+    # an item that wants neither product is skipped: nothing to launch, no device needed
+    assert L.flop_weight_grad_finish((W * 1)(item(dP=None, dQ=None)), 1, None) == 0
+    # the deferring call needs somewhere to put the item
+    assert L.flop_bwd_defer_weights(1, 2, 4, 4, 4, p, 4, p, 4, p, 4, p, 4, p, p, p, 4, p, 4, p, 4, p, 4, None, 0, p, 1 << 20,
+                                    None, None, None) == -1
+
+
 def test_status_strings(lib):
     seen = {flop.status_string(s) for s in range(0, -10, -1)}
     assert len(seen) == 10 and flop.status_string(0) == "ok"
