@@ -453,6 +453,8 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
     if want("C4"):
         n, d, r, dout = 8192, 3056, 3056, 9168
         for align, label in ((64, ", rows padded to 128 bytes"), (1, ", dense rows")):
+            if plain("C4") and align != 64:
+                continue
             ld = lambda c: -(-c // align) * align
             x, Q, P = (randn(n, d, 1.0, torch.bfloat16, ld(d)), randn(r, d, 1.0 / d, torch.bfloat16, ld(d)),
                        randn(dout, r, 1.0 / r, torch.bfloat16, ld(r)))
@@ -461,7 +463,8 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
             r_out = torch.empty(1, dtype=torch.int32, device=dev)
             idx = torch.empty(r, dtype=torch.int32, device=dev)
             Qc, Pc, zc = empty(r, d, torch.bfloat16, ld(d)), empty(dout, r, torch.bfloat16, ld(r)), torch.empty(r, device=dev)
-            for frac in (0.04, 0.1, 0.2, 0.35, 1.0):   # 0.04 (122 ranks) is beyond the configuration list: 96 % pruned
+            # 0.04 (122 ranks) is beyond the configuration list: 96 % pruned
+            for frac in ((0.2,) if plain("C4") else (0.04, 0.1, 0.2, 0.35, 1.0)):
                 if frac < 1.0:
                     keep = int(round(frac * r))
                     thr = float(np.log(-synth.L / synth.R))
@@ -554,8 +557,9 @@ def main() -> int:
     ap.add_argument("--trace-steps", type=int, default=20)
     ap.add_argument("--sweep", action="store_true", help="size sweep of the bandwidth-bound kernels instead of the step benchmark")
     ap.add_argument("--configs", action="store_true", help="time every workload configuration (C1..C5) instead of the step benchmark")
-    ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain and "
-                                               "C3:plain run the 128-byte-padded layout and the dense pass only (for profiler runs)")
+    ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain, "
+                                               "C3:plain and C4:plain run the 128-byte-padded layout only (wide: the dense pass, C4: 611 "
+                                               "ranks), so that a profiler run holds one launch per kernel and grid size")
     ap.add_argument("--force-shape", type=int, default=-1,
                     help="with --configs: block shape number (see flop_bench_tile_shape_name) for every bf16 transfer-kernel "
                          "launch instead of the library's choice; for profiler comparisons of shapes")
