@@ -82,7 +82,7 @@ struct AttrOnce {
 // by decreasing k extent so that the longest tiles are dispatched first.
 // lds_extra: what a launch with a B gathered along k adds for its table (only such launches ask for it)
 template <int ES, int BM, int BN>
-int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, int kernel_id, int threads,
+int launch_tiles(void (*kernel)(FLOP_HEAD_PARAMS, const GemmGroup), size_t lds, AttrOnce* attr, int kernel_id, int threads,
                  const GemmDesc* d_in, int count, hipStream_t stream, const BoundaryRider* rider = nullptr,
                  bool* carried = nullptr, size_t lds_extra = 0)
 {
@@ -174,12 +174,25 @@ int launch_tiles(void (*kernel)(const GemmGroup), size_t lds, AttrOnce* attr, in
         grp.rider_blocks = rider->bx * (rider->count + 1);
         if (carried) *carried = true;
     }
+    // the launch head (see LaunchHead): the first product as scalar arguments, when it is a plain one
+    LaunchHead head = {};
+    const GemmDesc& d0 = d[0];
+    if (!contiguous && !d0.seg && !d0.ext && !d0.b_map && d0.ksplit <= 1 && d0.lda <= 0xFFFFFFFFll && d0.ldb <= 0xFFFFFFFFll &&
+        grp.p[0].tiles_m * grp.p[0].tiles_n > 0) {
+        head.A = d0.A; head.B = d0.B;
+        head.lda = (uint32_t)d0.lda; head.ldb = (uint32_t)d0.ldb;
+        head.M = (int)d0.M; head.N = (int)d0.N; head.K = (int)d0.K;
+        head.flags = kHeadValid | (d0.a_kmajor ? kHeadAKmajor : 0) | (d0.b_kmajor ? kHeadBKmajor : 0);
+        head.next = grp.p[0].tiles_per_xcd;
+    }
     const dim3 grid((unsigned)(grp.tile_blocks + grp.rider_blocks));
     TraceSlot* ts = trace_acquire(kernel_id, tiles, flops);
     if (ts)   // the dispatch itself stamps the two events at kernel begin and end
-        hipExtLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, ts->start, ts->stop, 0, grp);
+        hipExtLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, ts->start, ts->stop, 0, head.A, head.B,
+                              head.lda, head.ldb, head.M, head.N, head.K, head.flags, head.next, grp);
     else
-        hipLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, grp);
+        hipLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, stream, head.A, head.B, head.lda, head.ldb, head.M,
+                           head.N, head.K, head.flags, head.next, grp);
     return hipGetLastError() == hipSuccess ? FLOP_OK : FLOP_ERR_HIP;
 }
 

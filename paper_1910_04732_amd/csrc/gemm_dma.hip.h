@@ -618,14 +618,17 @@ __device__ __forceinline__ void dma_main_loop(const GemmProblem& pr, unsigned ch
 }
 
 template <typename SH, bool BKM, int XFER = 16>
-__global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(const GemmGroup grp)
+__global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PARAMS, const GemmGroup grp)
 {
     constexpr int BM = SH::BM, BN = SH::BN, TM = SH::TM, TN = SH::TN, WTM = SH::WTM, WTN = SH::WTN;
     constexpr int THREADS = SH::THREADS, NWAVES = THREADS / 64;
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    if (grp.rider_blocks > 0 && (int)blockIdx.x >= grp.tile_blocks) {   // block-uniform
+    // (blocks of the first product do not look at the group before their main loop, see LaunchHead; the riders'
+    // block indices lie beyond every product's)
+    const bool head_block = (hflags & kHeadValid) != 0 && (int)(blockIdx.x >> 3) < hnext;
+    if (!head_block && grp.rider_blocks > 0 && (int)blockIdx.x >= grp.tile_blocks) {   // block-uniform
         // the step-boundary blocks are written for kStreamThreads threads; surplus wavefronts leave
         if (THREADS > kStreamThreads && (int)threadIdx.x >= kStreamThreads) return;
         const int id = (int)blockIdx.x - grp.tile_blocks;
@@ -634,7 +637,8 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(const GemmGr
     }
     GemmProblem pr;
     int tile_m, tile_n;
-    if (!(locate_tile<2, BM, BN>(grp, pr, tile_m, tile_n))) return;
+    bool from_head;
+    if (!(locate_tile<2, BM, BN>(FLOP_HEAD_ARGS, grp, pr, tile_m, tile_n, from_head))) return;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x;
@@ -666,9 +670,14 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(const GemmGr
             ktab = tab;
         }
     }
+    // the remaining fields of a head block's product: requested here, first needed after the main loop, so the
+    // trip to the kernel-argument segment passes while the first stages are on their way
+    constexpr bool kEarlyTail = SH::THREADS <= 384 && XFER == 16;   // (the other kernels have no registers to spare)
+    if (kEarlyTail && from_head) finish_problem(pr, grp.p[0]);
     if (pr.a_kmajor) dma_main_loop<SH, true, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
     else dma_main_loop<SH, false, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
     __syncthreads();
+    if (!kEarlyTail && from_head) finish_problem(pr, grp.p[0]);
 
     // ---- the groups' partial sums are added in group order (fixed, so the result is deterministic): groups
     // 1 .. G-1 leave theirs in LDS, lane-interleaved, group 0 adds them up and goes on alone

@@ -93,6 +93,25 @@ struct GemmGroup {
     int xcd_first[9];
 };
 
+// Head of a launch: what a block of the launch's first product needs to start its main loop, passed as leading
+// scalar kernel arguments.  The kernels are compiled with kernel-argument preloading, so these arrive in registers
+// with the wavefront, while the group itself (by value, in the kernel-argument segment) is a trip to memory away:
+// 1.4 us per block before the first transfer could be issued, measured with per-block timestamps, a quarter of a
+// launch of 8 us.  The rest of the first product's descriptor (output, scales, column sums) is read from the
+// group after the main loop.  Blocks of later products, and launches whose first product has device-side
+// extents, a gathered operand or a k split, take everything from the group as before (flags == 0).
+struct LaunchHead {
+    const void* A;
+    const void* B;
+    uint32_t lda, ldb;
+    int M, N, K;
+    int flags;   // kHeadValid | kHeadAKmajor | kHeadBKmajor
+    int next;    // per-XCD block indices below this belong to the first product (its tiles_per_xcd)
+};
+constexpr int kHeadValid = 1, kHeadAKmajor = 2, kHeadBKmajor = 4;
+#define FLOP_HEAD_PARAMS const void* hA, const void* hB, uint32_t hlda, uint32_t hldb, int hM, int hN, int hK, int hflags, int hnext
+#define FLOP_HEAD_ARGS LaunchHead{hA, hB, hlda, hldb, hM, hN, hK, hflags, hnext}
+
 // Tiles are numbered band by band: a band is kTileBand tile rows, walked column by
 // column, so that the tiles in flight on an XCD share few row and column panels.
 __device__ __forceinline__ void decode_tile(const GemmProblem& pr, int t, int& tile_m, int& tile_n)
@@ -111,27 +130,51 @@ __device__ __forceinline__ void decode_tile(const GemmProblem& pr, int t, int& t
 // in k extent).  Block b serves XCD b%8 with per-XCD index b/8; problems are
 // laid out one after another along that index, each padded to tiles_per_xcd
 // entries.  Returns false for padding blocks, which have no tile.
+// from_head: the problem was built from the launch head; its epilogue fields are still to be read (finish_problem)
 template <int ES, int BM, int BN>
-__device__ __forceinline__ bool locate_tile(const GemmGroup& grp, GemmProblem& pr, int& tile_m, int& tile_n)
+__device__ __forceinline__ bool locate_tile(const LaunchHead& head, const GemmGroup& grp, GemmProblem& pr, int& tile_m,
+                                            int& tile_n, bool& from_head)
 {
     const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
+    from_head = (head.flags & kHeadValid) != 0 && i < head.next;
+    if (from_head) {
+        pr = GemmProblem{};
+        pr.A = head.A; pr.B = head.B;
+        pr.lda = head.lda; pr.ldb = head.ldb;
+        pr.M = head.M; pr.N = head.N; pr.K = head.K;
+        pr.tiles_m = (head.M + BM - 1) / BM;
+        pr.tiles_n = (head.N + BN - 1) / BN;
+        pr.tiles_per_xcd = head.next;
+        pr.a_kmajor = (head.flags & kHeadAKmajor) != 0;
+        pr.b_kmajor = (head.flags & kHeadBKmajor) != 0;
+        const int t = xcd * head.next + i;
+        if (t >= pr.tiles_m * pr.tiles_n) return false;
+        decode_tile(pr, t, tile_m, tile_n);
+        return true;
+    }
     if (grp.contiguous) {
         // One sequence of tiles cut into eight contiguous pieces of equal work: a product lies on as few XCDs as
         // its size allows, so that its operand panels are fetched into few L2s (weight-gradient products of many
         // layers in one launch: every operand is as long as the token count and used by one product only).
         const int pos = grp.xcd_first[xcd] + i;
         if (pos >= grp.xcd_first[xcd + 1]) return false;
+        pr = grp.p[0];
         int q = 0;
 #pragma unroll
         for (int j = 1; j < kMaxGroup; ++j) q += (j < grp.count && pos >= grp.p[j].xcd_begin) ? 1 : 0;
-        pr = grp.p[q];
+        if (q != 0) pr = grp.p[q];
         decode_tile(pr, pos - pr.xcd_begin, tile_m, tile_n);
         return true;
     }
+    // The group lies in the kernel-argument segment, a trip to memory away (0.8 us measured per dependent load at the
+    // start of a block).  The first product's descriptor is fetched together with the products' starting
+    // positions instead of after them: that is the only product of a forward launch and, products being ordered by
+    // k extent, the one with the longest tiles of a grouped launch; only blocks of later products pay a second trip.
+    pr = grp.p[0];
     int q = 0;   // xcd_begin ascends: the problem's index is the number of later problems that start at or before i
 #pragma unroll
     for (int j = 1; j < kMaxGroup; ++j) q += (j < grp.count && i >= grp.p[j].xcd_begin) ? 1 : 0;
-    pr = grp.p[q];
+    if (q != 0) pr = grp.p[q];
     // Extents known only on the device shrink the problem first, so that the tiles that remain
     // are again spread evenly over the XCDs (the grid was sized for the host's upper bounds).
     if (pr.seg) {
@@ -172,6 +215,18 @@ __device__ __forceinline__ bool locate_tile(const GemmGroup& grp, GemmProblem& p
     }
     decode_tile(pr, t, tile_m, tile_n);
     return true;
+}
+
+// The fields of the first product that its blocks did not need before the main loop (see LaunchHead).
+__device__ __forceinline__ void finish_problem(GemmProblem& pr, const GemmProblem& g)
+{
+    pr.C = g.C; pr.ldc = g.ldc;
+    pr.col_scale = g.col_scale;
+    pr.gate_alpha = g.gate_alpha; pr.gate_u = g.gate_u;
+    pr.gate_beta = g.gate_beta; pr.gate_l = g.gate_l; pr.gate_r = g.gate_r;
+    pr.c_rowmap = g.c_rowmap;
+    pr.a_vec = g.a_vec; pr.b_vec = g.b_vec;
+    pr.dot = g.dot; pr.lddot = g.lddot; pr.dot_partial = g.dot_partial; pr.dot_ld = g.dot_ld;
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
@@ -297,7 +352,7 @@ struct TileStager {
 // whole tile), which lets the tile be as small as one 32x32 matrix instruction: the products of a 256 x 512 layer
 // are then 128 tiles instead of 32, and a tile's arithmetic is spread over sixteen wavefronts.
 template <typename T, int BM, int BN, int G = 1, int KW = 1>
-__global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(const GemmGroup grp)
+__global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(FLOP_HEAD_PARAMS, const GemmGroup grp)
 {
     constexpr int ES = sizeof(T);
     constexpr int BK = kStepBytes / ES;
@@ -313,7 +368,9 @@ __global__ __launch_bounds__(kGemmThreads * G) void gemm_tile_kernel(const GemmG
     // ---- which problem, which tile -------------------------------------
     GemmProblem pr;
     int tile_m, tile_n;
-    if (!(locate_tile<ES, BM, BN>(grp, pr, tile_m, tile_n))) return;
+    bool from_head;
+    if (!(locate_tile<ES, BM, BN>(FLOP_HEAD_ARGS, grp, pr, tile_m, tile_n, from_head))) return;
+    if (from_head) finish_problem(pr, grp.p[0]);   // (this kernel's loads need a_vec / b_vec at once)
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int group = (int)threadIdx.x / kGemmThreads;   // wave-uniform
