@@ -803,7 +803,7 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PA
             const int64_t orow = pr.c_rowmap ? pr.c_rowmap[row] : row;
             uint16_t* dst = (uint16_t*)pr.C + orow * pr.ldc + ccol;
             if (c_vec && ccol + 8 <= pr.N) {
-                *(u32x4*)dst = v;
+                __builtin_nontemporal_store(v, (u32x4*)dst);
             } else if (c_word && ccol + 8 <= pr.N) {
                 ((uint32_t*)dst)[0] = v[0]; ((uint32_t*)dst)[1] = v[1];
                 ((uint32_t*)dst)[2] = v[2]; ((uint32_t*)dst)[3] = v[3];
