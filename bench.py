@@ -545,6 +545,45 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
     return 0
 
 
+def phases(flop, step, torch) -> int:
+    """Where the time of a launch goes, block by block (measurement build of the library): every block of the step's
+    eight launches records the 100 MHz wall clock at entry, before its main loop, after it, after staging its output
+    tile and after its stores have completed.  One table row per launch, times in us as 5th / 50th / 95th percentile
+    over the launch's blocks; `span` = first block entry to last block end."""
+    import numpy as np
+    names = ["g1 = (x Q1^T) z1 (+ gates, Eq.(3))", "y1 = g1 P1^T", "g2 = (y1' Q2^T) z2", "y2 = g2 P2^T", "{dh2, dP2}", "{dQ2, dx2}",
+             "{dh1, dP1}", "{dQ1, dx1} (+ gate-gradient finish)"]
+    reps = 20
+    acc = None
+    kinds = None
+    for _ in range(reps):
+        flop.flop_trace_begin(16)
+        flop.flop_bench_phases_begin()
+        step()
+        torch.cuda.synchronize()
+        recs = flop.flop_trace_end(16)
+        rows = []
+        for launch in range(8):
+            p = flop.flop_bench_phases_read(launch) * 10.0   # ns
+            p = p[p[:, 0] > 0]
+            t0 = p[:, 0].min()
+            pc = lambda a: [float(np.percentile(a, q)) / 1e3 for q in (5, 50, 95)]
+            rows.append([len(p), (p[:, 4].max() - t0) / 1e3] + pc(p[:, 1] - p[:, 0]) + pc(p[:, 2] - p[:, 1]) + pc(p[:, 3] - p[:, 2]) +
+                        pc(p[:, 4] - p[:, 3]) + [recs[launch][3] * 1e3])
+        kinds = [kernel_name(r[0]) for r in recs[:8]]
+        acc = np.array(rows) if acc is None else acc + np.array(rows)
+    acc /= reps
+    print("launch                               kernel                           blocks  span   entry->loop       main loop (incl. first load)  staging           stores            begin/end events")
+    for nm, kd, r in zip(names, kinds, acc):
+        f3 = lambda v: "%5.1f /%5.1f /%5.1f" % tuple(v)
+        print("%-36s %-32s %6d %5.1f   %s   %s           %s   %s   %6.1f" % (nm, kd.replace("gemm_bf16_dma_kernel", ""), round(r[0]), r[1], f3(r[2:5]), f3(r[5:8]),
+                                                                        f3(r[8:11]), f3(r[11:14]), r[14]))
+    print("(us; p5 / median / p95 over the launch's blocks, mean of %d steps; span = first block's entry to last block's end; the last "
+          "column is the launch's duration from the dispatch's own begin/end events: what lies between it and the span is "
+          "dispatch and completion outside the blocks)" % reps)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -555,6 +594,9 @@ def main() -> int:
                          "through the C ABI; replays measured a few per cent slower on this stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-steps", type=int, default=20)
+    ap.add_argument("--phases", action="store_true",
+                    help="per-block phase times of the step's eight launches (entry, main loop, staging, stores) from the "
+                         "measurement build of the library (libflop_hip_phases.so) instead of the step benchmark")
     ap.add_argument("--sweep", action="store_true", help="size sweep of the bandwidth-bound kernels instead of the step benchmark")
     ap.add_argument("--configs", action="store_true", help="time every workload configuration (C1..C5) instead of the step benchmark")
     ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain, "
@@ -581,6 +623,11 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.phases:
+        if not os.path.exists(flop.LIB_PATH_PHASES):
+            print("bench.py: %s is missing (python -c 'import __graft_entry__ as g; g.build()')" % flop.LIB_PATH_PHASES, file=sys.stderr)
+            return 3
+        flop.LIB_PATH = flop.LIB_PATH_PHASES
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     hc = flop.flop_hc(synth.BETA, synth.L, synth.R)
@@ -641,6 +688,8 @@ def main() -> int:
     torch.cuda.synchronize()
     outs = lambda: [l0.clone(), dalpha.clone(), z.clone(), dzda.clone()] + \
         [t[k].clone() for t in layers for k in ("y", "dx", "dQ", "dP")]
+    if args.phases:
+        return phases(flop, step, torch)
     eager_ref = outs()
     mode = "eager"
     run = lambda k: [step() for _ in range(k)]

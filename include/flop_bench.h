@@ -46,6 +46,20 @@ int flop_mfma_probe(flop_dtype dt, int64_t iters, int32_t blocks, float* sink, d
  * ("64x96 g2": 64 x 96 tile, two k groups).  Results do not depend on the shape beyond float32 summation order.
  */
 int flop_bench_force_tile_shape(int shape);
+
+/*
+ * Per-block phase times of the bfloat16 transfer kernel, in the measurement build of the library only
+ * (paper_1910_04732_amd/libflop_hip_phases.so: the same sources compiled with -DFLOP_PHASE_STAMPS, in which the
+ * first thread of every block records the 100 MHz wall clock at block entry, before its main loop, after it, after
+ * its output tile is staged in LDS, and after its stores have completed).  flop_bench_phases_begin() clears the
+ * record and restarts the launch count: the following launches of that kernel take the slots 0, 1, ... 15 in
+ * order (later launches and blocks beyond 4096 per launch are not recorded).  flop_bench_phases_read(launch,
+ * stamps, max_blocks) synchronises the device and copies 5 stamps per block of that launch to host memory (all
+ * zero for a block that recorded nothing: padding blocks, riders, k-split launches); returns the number of blocks
+ * copied.  In the product library (no stamps compiled in) both return FLOP_ERR_PARAM.
+ */
+int flop_bench_phases_begin(void);
+int flop_bench_phases_read(int launch, unsigned long long* stamps, int max_blocks);
 int flop_bench_tile_shapes(void);
 const char* flop_bench_tile_shape_name(int shape);
 

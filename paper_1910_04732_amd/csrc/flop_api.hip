@@ -78,6 +78,11 @@ struct AttrOnce {
     void done(int dev) { devices.fetch_or(1ull << (dev & 63), std::memory_order_release); }
 };
 
+#ifdef FLOP_PHASE_STAMPS
+// Measurement build: launches of the transfer kernel take the stamp slots 0, 1, ... after flop_bench_phases_begin()
+std::atomic<int> g_stamp_launches{kStampSlots};
+#endif
+
 // One launch of a tile kernel over up to kMaxGroup products.  Products are ordered
 // by decreasing k extent so that the longest tiles are dispatched first.
 // lds_extra: what a launch with a B gathered along k adds for its table (only such launches ask for it)
@@ -185,6 +190,13 @@ int launch_tiles(void (*kernel)(FLOP_HEAD_PARAMS, const GemmGroup), size_t lds, 
         head.flags = kHeadValid | (d0.a_kmajor ? kHeadAKmajor : 0) | (d0.b_kmajor ? kHeadBKmajor : 0);
         head.next = grp.p[0].tiles_per_xcd;
     }
+#ifdef FLOP_PHASE_STAMPS
+    grp.stamp_slot = -1;
+    if (kernel_id % 1000 >= 100) {   // the transfer kernel
+        const int slot = g_stamp_launches.fetch_add(1);
+        if (slot < kStampSlots) grp.stamp_slot = slot;
+    }
+#endif
     const dim3 grid((unsigned)(grp.tile_blocks + grp.rider_blocks));
     TraceSlot* ts = trace_acquire(kernel_id, tiles, flops);
     if (ts)   // the dispatch itself stamps the two events at kernel begin and end
@@ -1894,6 +1906,37 @@ int flop_embed_bwd(flop_dtype dt, int64_t n_tokens, int32_t n_clusters, const fl
         }
     }
     return FLOP_OK;
+}
+
+int flop_bench_phases_begin(void)
+{
+#ifdef FLOP_PHASE_STAMPS
+    if (hipDeviceSynchronize() != hipSuccess) return FLOP_ERR_HIP;
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(flop::g_phase_stamps)) != hipSuccess) return FLOP_ERR_HIP;
+    if (hipMemset(p, 0, sizeof(unsigned long long) * kStampSlots * kStampBlocks * kStampPhases) != hipSuccess) return FLOP_ERR_HIP;
+    g_stamp_launches.store(0);
+    return FLOP_OK;
+#else
+    return FLOP_ERR_PARAM;
+#endif
+}
+
+int flop_bench_phases_read(int launch, unsigned long long* stamps, int max_blocks)
+{
+#ifdef FLOP_PHASE_STAMPS
+    if (launch < 0 || launch >= kStampSlots || max_blocks < 0) return FLOP_ERR_SHAPE;
+    if (!stamps) return FLOP_ERR_NULL;
+    if (hipDeviceSynchronize() != hipSuccess) return FLOP_ERR_HIP;
+    const int blocks = max_blocks < kStampBlocks ? max_blocks : kStampBlocks;
+    if (hipMemcpyFromSymbol(stamps, HIP_SYMBOL(flop::g_phase_stamps), sizeof(unsigned long long) * blocks * kStampPhases,
+                            sizeof(unsigned long long) * (size_t)launch * kStampBlocks * kStampPhases) != hipSuccess)
+        return FLOP_ERR_HIP;
+    return blocks;
+#else
+    (void)launch; (void)stamps; (void)max_blocks;
+    return FLOP_ERR_PARAM;
+#endif
 }
 
 }  // extern "C"

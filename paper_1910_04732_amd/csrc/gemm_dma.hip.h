@@ -617,9 +617,19 @@ __device__ __forceinline__ void dma_main_loop(const GemmProblem& pr, unsigned ch
     loop.run(acc);
 }
 
+// Measurement build (-DFLOP_PHASE_STAMPS, see flop_bench_phases_read): five wall-clock stamps per block.
+#ifdef FLOP_PHASE_STAMPS
+constexpr int kStampSlots = 16, kStampBlocks = 4096, kStampPhases = 5;
+__device__ unsigned long long g_phase_stamps[kStampSlots * kStampBlocks * kStampPhases];
+#define FLOP_STAMP(name) const unsigned long long name = wall_clock64()
+#else
+#define FLOP_STAMP(name)
+#endif
+
 template <typename SH, bool BKM, int XFER = 16>
 __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PARAMS, const GemmGroup grp)
 {
+    FLOP_STAMP(stamp_entry);
     constexpr int BM = SH::BM, BN = SH::BN, TM = SH::TM, TN = SH::TN, WTM = SH::WTM, WTN = SH::WTN;
     constexpr int THREADS = SH::THREADS, NWAVES = THREADS / 64;
 
@@ -672,11 +682,13 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PA
     }
     // the remaining fields of a head block's product: requested here, first needed after the main loop, so the
     // trip to the kernel-argument segment passes while the first stages are on their way
+    FLOP_STAMP(stamp_setup);
     constexpr bool kEarlyTail = SH::THREADS <= 384 && XFER == 16;   // (the other kernels have no registers to spare)
     if (kEarlyTail && from_head) finish_problem(pr, grp.p[0]);
     if (pr.a_kmajor) dma_main_loop<SH, true, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
     else dma_main_loop<SH, false, BKM, XFER>(pr, smem, m0, n0, group, ktab, acc);
     __syncthreads();
+    FLOP_STAMP(stamp_loop);
     if (!kEarlyTail && from_head) finish_problem(pr, grp.p[0]);
 
     // ---- the groups' partial sums are added in group order (fixed, so the result is deterministic): groups
@@ -788,6 +800,7 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PA
         }
     }
     __syncthreads();
+    FLOP_STAMP(stamp_staged);
     const bool c_vec = (((uintptr_t)pr.C & 15u) == 0) && (pr.ldc % 8 == 0);
     const bool c_word = (((uintptr_t)pr.C & 3u) == 0) && (pr.ldc % 2 == 0);   // rows 4-byte aligned
     float ds[8];
@@ -839,6 +852,13 @@ __global__ __launch_bounds__(SH::THREADS) void gemm_bf16_dma_kernel(FLOP_HEAD_PA
             pr.dot_partial[(int64_t)tile_m * pr.dot_ld + n0 + tid] = tot;
         }
     }
+#ifdef FLOP_PHASE_STAMPS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the block's stores have been acknowledged
+    if (threadIdx.x == 0 && grp.stamp_slot >= 0 && grp.stamp_slot < kStampSlots && (int)blockIdx.x < kStampBlocks) {
+        unsigned long long* o = g_phase_stamps + ((size_t)grp.stamp_slot * kStampBlocks + blockIdx.x) * kStampPhases;
+        o[0] = stamp_entry; o[1] = stamp_setup; o[2] = stamp_loop; o[3] = stamp_staged; o[4] = wall_clock64();
+    }
+#endif
 }
 
 template <typename SH>

@@ -91,6 +91,9 @@ struct GemmGroup {
     // xcd_first[x] .. xcd_first[x + 1] - 1; p[q].xcd_begin is then product q's first position in that sequence.
     int contiguous;
     int xcd_first[9];
+#ifdef FLOP_PHASE_STAMPS
+    int stamp_slot;   // measurement build: where this launch's blocks record their phase times, or -1
+#endif
 };
 
 // Head of a launch: what a block of the launch's first product needs to start its main loop, passed as leading

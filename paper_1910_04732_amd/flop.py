@@ -137,6 +137,8 @@ def lib():
                      "flop_fwd_active_indexed", "flop_bwd_active_indexed"):
             getattr(L, name).restype = _int
         L.flop_bench_force_tile_shape.argtypes = [_int]
+        L.flop_bench_phases_begin.argtypes = []
+        L.flop_bench_phases_read.argtypes = [_int, _vp, _int]
         L.flop_bench_force_tile_shape.restype = _int
         L.flop_bench_tile_shapes.restype = _int
         L.flop_bench_tile_shape_name.argtypes = [_int]
@@ -585,6 +587,24 @@ def flop_bench_force_tile_shape(shape: int):
 def flop_bench_tile_shapes():
     """Names of the block shapes, indexed by shape number."""
     return [lib().flop_bench_tile_shape_name(i).decode() for i in range(lib().flop_bench_tile_shapes())]
+
+
+LIB_PATH_PHASES = os.path.join(_HERE, "libflop_hip_phases.so")   # measurement build (see include/flop_bench.h)
+
+
+def flop_bench_phases_begin():
+    """Measurement build only: clears the per-block phase stamps; the next 16 transfer-kernel launches record."""
+    _check(lib().flop_bench_phases_begin(), "flop_bench_phases_begin")
+
+
+def flop_bench_phases_read(launch: int, max_blocks: int = 4096):
+    """Measurement build only: ``(blocks, 5)`` int64 array of 100 MHz wall-clock stamps of launch ``launch``
+    (entry, before the main loop, after it, output staged, stores complete); rows of zeros: blocks without a tile."""
+    import numpy as np
+    buf = np.zeros((max_blocks, 5), dtype=np.uint64)
+    n = lib().flop_bench_phases_read(int(launch), buf.ctypes.data, int(max_blocks))
+    _check(min(n, 0), "flop_bench_phases_read")
+    return buf[:n].astype(np.int64)
 
 
 def flop_trace_begin(capacity: int):

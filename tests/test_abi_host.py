@@ -85,6 +85,13 @@ def test_pending_weight_gradients_are_validated_before_any_launch(lib):
                                     None, None, None) == -1
 
 
+def test_phase_stamps_exist_only_in_the_measurement_build(lib):
+    """The product library has no stamps compiled into its kernels and says so."""
+    buf = (ctypes.c_ulonglong * 10)()
+    assert lib.flop_bench_phases_begin() == -5
+    assert lib.flop_bench_phases_read(0, ctypes.cast(buf, ctypes.c_void_p), 2) == -5
+
+
 def test_status_strings(lib):
     seen = {flop.status_string(s) for s in range(0, -10, -1)}
     assert len(seen) == 10 and flop.status_string(0) == "ok"
