@@ -25,5 +25,6 @@ def test_phase_report_of_the_benchmark_step():
         blocks, span, event = int(f[0]), float(f[1]), float(f[-1])
         phases = [float(v) for v in f[2:-1]]
         assert blocks >= 192 and len(phases) == 12 and all(v > 0.0 for v in phases)
-        # median phase times of a block add up to less than the launch's span, the span to about the event time
-        assert sum(phases[1::3]) <= span * 1.05 and span <= event * 1.25
+        # a block's median phase times fit into the launch's span, and the span into about the launch's own
+        # begin/end events (wide margins: the figures are timings)
+        assert sum(phases[1::3]) <= span * 1.25 and span <= event * 2.0
