@@ -499,6 +499,26 @@ def test_gate_grad_standalone(dtype, shape):
     assert_close(to_np(da) - 2.0, want["dalpha"], TOL[dtype] if dtype == "bf16" else 2e-5, "dlog_alpha")
 
 
+@pytest.mark.parametrize("dtype,n,r,ld", [("bf16", 130, 2056, 2056), ("bf16", 70, 2051, 2056), ("f32", 37, 1030, 1032),
+                                          ("f32", 300, 1024, 1024), ("bf16", 16500, 2048, 2048)],
+                         ids=lambda v: str(v))
+def test_gate_grad_long_rows(dtype, n, r, ld):
+    """Long rows in 16-byte aligned storage through the column-sum kernel: many block columns, whole and partial last
+    column groups (row length not a multiple of 16 bytes inside padded rows), chunks of 32 and (from 16384 rows) 128
+    rows with ragged last chunks."""
+    c = synth.layer_inputs(760 + n, n, 24, r, 16, dtype)
+    z, dzda = oracle.gate_sample(c["log_alpha"], c["u"], BETA, L, R)
+    h, g, _ = oracle.fwd(c["x"], c["Q"], c["P"], z)
+    want = oracle.bwd(c["dy"], c["x"], c["Q"], c["P"], z, dzda)
+    dg = c["dy"] @ c["P"]
+    dh64, g64 = synth.round_storage(dg * z, dtype), synth.round_storage(g, dtype)
+    dh_t, g_t = padded(to_dev(dh64, dtype), ld), padded(to_dev(g64, dtype), ld)
+    da = torch.full((r,), float("nan"), device=dev())
+    ws = flop.workspace(flop.flop_workspace_bytes(flop.FLOP_OP_GATE_GRAD, flop._dt(g_t), n, 0, r, 0), dev())
+    flop.flop_gate_grad(dh_t, g_t, to_dev(z), to_dev(dzda), da, ws)
+    assert_close(to_np(da), want["dalpha"], TOL[dtype] if dtype == "bf16" else 2e-5, "dlog_alpha")
+
+
 # ------------------------------------------------- tied adaptive softmax side ---
 def test_tied_softmax_cluster_shapes():
     """Section 4.2 on the output side: the logits of a vocabulary cluster are a gated
