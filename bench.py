@@ -545,7 +545,7 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
     return 0
 
 
-def phases(flop, step, torch) -> int:
+def phases(flop, step, torch, cold=False) -> int:
     """Where the time of a launch goes, block by block (measurement build of the library): every block of the step's
     eight launches records the 100 MHz wall clock at entry, before its main loop, after it, after staging its output
     tile and after its stores have completed.  One table row per launch, times in us as 5th / 50th / 95th percentile
@@ -556,7 +556,13 @@ def phases(flop, step, torch) -> int:
     reps = 20
     acc = None
     kinds = None
+    # --cold: 512 MB are overwritten before every measured step, so that the step's operands come from HBM instead
+    # of the 256 MB Infinity Cache (where a training loop over this workload finds them)
+    big = torch.empty(1 << 29, dtype=torch.uint8, device="cuda:0") if cold else None
     for _ in range(reps):
+        if cold:
+            big.fill_(1)
+            torch.cuda.synchronize()
         flop.flop_trace_begin(16)
         flop.flop_bench_phases_begin()
         step()
@@ -597,6 +603,7 @@ def main() -> int:
     ap.add_argument("--phases", action="store_true",
                     help="per-block phase times of the step's eight launches (entry, main loop, staging, stores) from the "
                          "measurement build of the library (libflop_hip_phases.so) instead of the step benchmark")
+    ap.add_argument("--cold", action="store_true", help="with --phases: evict the operands from the last-level cache before every measured step")
     ap.add_argument("--sweep", action="store_true", help="size sweep of the bandwidth-bound kernels instead of the step benchmark")
     ap.add_argument("--configs", action="store_true", help="time every workload configuration (C1..C5) instead of the step benchmark")
     ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain, "
@@ -689,7 +696,7 @@ def main() -> int:
     outs = lambda: [l0.clone(), dalpha.clone(), z.clone(), dzda.clone()] + \
         [t[k].clone() for t in layers for k in ("y", "dx", "dQ", "dP")]
     if args.phases:
-        return phases(flop, step, torch)
+        return phases(flop, step, torch, args.cold)
     eager_ref = outs()
     mode = "eager"
     run = lambda k: [step() for _ in range(k)]
