@@ -117,8 +117,12 @@ constexpr int kHeadValid = 1, kHeadAKmajor = 2, kHeadBKmajor = 4;
 
 // Tiles are numbered band by band: a band is kTileBand tile rows, walked column by
 // column, so that the tiles in flight on an XCD share few row and column panels.
+template <int BM, int BN>
 __device__ __forceinline__ void decode_tile(const GemmProblem& pr, int t, int& tile_m, int& tile_n)
 {
+    // a tile twice as tall as wide has row panels twice the size of its column panels: half as many tile rows per band
+    // keep the bytes of the panels that the tiles in flight on an XCD share at their minimum
+    constexpr int kTileBand = BM > BN ? flop::kTileBand / 2 : flop::kTileBand;
     const int band_tiles = kTileBand * pr.tiles_n;
     const int band = t / band_tiles, in_band = t - band * band_tiles;
     const int rows_here = min(kTileBand, pr.tiles_m - band * kTileBand);
@@ -152,7 +156,7 @@ __device__ __forceinline__ bool locate_tile(const LaunchHead& head, const GemmGr
         pr.b_kmajor = (head.flags & kHeadBKmajor) != 0;
         const int t = xcd * head.next + i;
         if (t >= pr.tiles_m * pr.tiles_n) return false;
-        decode_tile(pr, t, tile_m, tile_n);
+        decode_tile<BM, BN>(pr, t, tile_m, tile_n);
         return true;
     }
     if (grp.contiguous) {
@@ -166,7 +170,7 @@ __device__ __forceinline__ bool locate_tile(const LaunchHead& head, const GemmGr
 #pragma unroll
         for (int j = 1; j < kMaxGroup; ++j) q += (j < grp.count && pos >= grp.p[j].xcd_begin) ? 1 : 0;
         if (q != 0) pr = grp.p[q];
-        decode_tile(pr, pos - pr.xcd_begin, tile_m, tile_n);
+        decode_tile<BM, BN>(pr, pos - pr.xcd_begin, tile_m, tile_n);
         return true;
     }
     // The group lies in the kernel-argument segment, a trip to memory away (0.8 us measured per dependent load at the
@@ -216,7 +220,7 @@ __device__ __forceinline__ bool locate_tile(const LaunchHead& head, const GemmGr
         pr.K = k_here;
         pr.split_out += (int64_t)slice * pr.M * pr.N;
     }
-    decode_tile(pr, t, tile_m, tile_n);
+    decode_tile<BM, BN>(pr, t, tile_m, tile_n);
     return true;
 }
 
