@@ -57,10 +57,10 @@ def kernel_name(kid: int) -> str:
 TRAFFIC_SOURCE = "profiles/contraction_kernels_C2_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, taken offline; not measured by this run)"
 TRAFFIC_BYTES_PER_LAUNCH = {
     "gemm_bf16_dma_kernel<64x96>": 1.458e+07,
-    "gemm_bf16_dma_kernel<128x128>": 5.132e+07,
-    "gemm_bf16_dma_kernel<64x96 g2>": 4.756e+07,
+    "gemm_bf16_dma_kernel<128x128>": 5.13e+07,
+    "gemm_bf16_dma_kernel<64x96 g2>": 4.757e+07,
     "gemm_bf16_dma_kernel<64x64>": 3.582e+07,
-    "gemm_bf16_dma_kernel<128x64>": 1.148e+08,
+    "gemm_bf16_dma_kernel<128x64>": 9.372e+07,
 }
 
 
