@@ -494,17 +494,6 @@ __global__ __launch_bounds__(kStreamThreads) void gather_rows_kernel(
 constexpr int kScatterWindow = 32;
 constexpr int kScatterThreads = 256;
 
-// Index of the run that contains sorted position pos (run_start ascending, run_start[nu] = valid).
-__device__ __forceinline__ int run_of(const int32_t* __restrict__ run_start, int nu, int pos)
-{
-    int lo = 0, hi = nu - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (run_start[mid] <= pos) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
 template <int ES>
 __device__ __forceinline__ float load_elem(const char* p, int64_t idx)
 {
@@ -583,14 +572,15 @@ __global__ __launch_bounds__(kScatterThreads) void embed_scatter_window_kernel(
 template <int ES>
 __global__ __launch_bounds__(kScatterThreads) void embed_scatter_join_kernel(
     EmbedClusterArgs cl, const int32_t* __restrict__ rows, const int32_t* __restrict__ seg,
-    const int32_t* __restrict__ run_start, const float* __restrict__ head, const float* __restrict__ tail, int64_t ldp)
+    const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_id, const float* __restrict__ head,
+    const float* __restrict__ tail, int64_t ldp)
 {
-    const int valid = seg[kSegValid], nu = seg[kSegUnique];
+    const int valid = seg[kSegValid];
     const int w0 = blockIdx.x * kScatterWindow;
     if (w0 >= valid) return;
     const int w1 = (w0 + kScatterWindow < valid) ? w0 + kScatterWindow : valid;
     // the run that leaves this window through its end, if it also starts here
-    const int u = run_of(run_start, nu, w1 - 1);
+    const int u = run_id[w1 - 1];
     const int r0 = run_start[u], r1 = run_start[u + 1];
     if (r0 < w0 || r1 <= w1) return;
     const int c = cluster_at(seg, cl.count, r0);

@@ -614,8 +614,10 @@ __device__ __forceinline__ void compact_col_body(
     int t0 = 0;   // first survivor with idx >= chunk start
     for (int c0 = 0; c0 < r && t0 < rp; c0 += kColChunk) {
         const int c1 = min(r, c0 + kColChunk);
-        // number of survivors below c1 (same search in every thread)
+        // number of survivors below c1 (same search in every thread; every survivor lies below r, so the last
+        // piece - the only one of a row of up to kColChunk columns - needs no search: a dozen dependent loads saved)
         int lo = t0, hi = rp;
+        if (c1 >= r) lo = rp;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
             if (idx[mid] < c1) lo = mid + 1; else hi = mid;
