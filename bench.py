@@ -35,6 +35,19 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
+def ramp_clocks(fn, torch, ms=200.0):
+    """Untimed passes of `fn` for `ms` of wall time.  The card leaves its idle power state only after some tenths of
+    a second of load (kernels of the first milliseconds run ~10 % longer than in the steady state a training loop
+    sees), and it falls back while the host prepares the next case."""
+    t0 = time.perf_counter()
+    while True:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+        if (time.perf_counter() - t0) * 1e3 >= ms:
+            return
+
+
 def kernel_name(kid: int) -> str:
     """Kernel behind a flop_trace kernel_id (10000 * (k groups - 1) + 1000 * dtype + 100 * transfer kernel + mean tile edge)."""
     groups, kid = kid // 10000 + 1, kid % 10000
@@ -56,11 +69,11 @@ def kernel_name(kid: int) -> str:
 # refreshed (profiles/ gives the command) whenever the tile choice of a launch changes.
 TRAFFIC_SOURCE = "profiles/contraction_kernels_C2_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, taken offline; not measured by this run)"
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "gemm_bf16_dma_kernel<64x96>": 1.458e+07,
+    "gemm_bf16_dma_kernel<64x96>": 1.456e+07,
     "gemm_bf16_dma_kernel<128x128>": 5.13e+07,
-    "gemm_bf16_dma_kernel<64x96 g2>": 4.757e+07,
+    "gemm_bf16_dma_kernel<64x96 g2>": 4.756e+07,
     "gemm_bf16_dma_kernel<64x64>": 3.582e+07,
-    "gemm_bf16_dma_kernel<128x64>": 9.372e+07,
+    "gemm_bf16_dma_kernel<128x64>": 9.408e+07,
 }
 
 
@@ -78,9 +91,7 @@ def sweep() -> int:
     hc = flop.flop_hc(synth.BETA, synth.L, synth.R)
 
     def timeit(fn, iters=20):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
+        ramp_clocks(fn, torch)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
@@ -202,9 +213,7 @@ def configs(only: str = "", no_cpu: bool = False, force_shape: int = -1) -> int:
         median = minimum = 0.0
 
     def timeit(fn, iters, graph=False):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
+        ramp_clocks(fn, torch)
         if graph:   # one pass captured into a HIP graph, replays timed
             cg = torch.cuda.CUDAGraph()
             with torch.cuda.graph(cg):
@@ -559,7 +568,10 @@ def phases(flop, step, torch, cold=False) -> int:
     # --cold: 512 MB are overwritten before every measured step, so that the step's operands come from HBM instead
     # of the 256 MB Infinity Cache (where a training loop over this workload finds them)
     big = torch.empty(1 << 29, dtype=torch.uint8, device="cuda:0") if cold else None
+    ramp_clocks(step, torch)
     for _ in range(reps):
+        for _ in range(20):   # the read-back below idles the card: a burst of untimed steps keeps its clocks up
+            step()
         if cold:
             big.fill_(1)
             torch.cuda.synchronize()
@@ -598,6 +610,8 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph and time replays (default: every step is issued "
                          "through the C ABI; replays measured a few per cent slower on this stack)")
+    ap.add_argument("--ramp-ms", type=float, default=500.0,
+                    help="wall time of untimed steps before the warm-up, so that the clocks have left the idle state (0: none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-steps", type=int, default=20)
     ap.add_argument("--phases", action="store_true",
@@ -719,6 +733,15 @@ def main() -> int:
         run = lambda k: [graph.replay() for _ in range(k)]
         mode = "hipgraph"
 
+    # The card leaves its idle power state only after some tenths of a second of load: kernels of the first few
+    # milliseconds run ~10 % longer than in the steady state that a training loop sees.  Untimed steps for
+    # --ramp-ms of wall time come first (reported in the line), then the W warm-up steps and the K timed ones.
+    ramp_steps = 0
+    t_ramp = time.perf_counter()
+    while (time.perf_counter() - t_ramp) * 1e3 < args.ramp_ms:
+        run(50)
+        torch.cuda.synchronize()
+        ramp_steps += 50
     run(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -814,7 +837,8 @@ def main() -> int:
         "config": {"workload": "C2: BERT-base-shaped FFN pair, 2048 tokens, 768->3072->768, rank 768, "
                                "train-mode gates, gate + fwd + bwd + expected-L0 per step",
                    "tokens": 2048, "rank": 768, "launch": mode, "launches_per_step": 8, "flops_per_step": flops_step,
-                   "frac_mfma_peak": round(tflops / PEAK_TFLOPS["bf16"], 4)},
+                   "frac_mfma_peak": round(tflops / PEAK_TFLOPS["bf16"], 4),
+                   "clock_ramp": {"ms": args.ramp_ms, "untimed_steps_before_warmup": ramp_steps}},
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": {"note": "the paper's own speed figures, end to end on whole models after pruning, hardware unnamed, "
                                   "precision unstated: context only, not this metric (Section 7, speed analysis; inference-time table)",
