@@ -427,11 +427,14 @@ __global__ __launch_bounds__(128) void embed_gather_gate_kernel(
     EmbedClusterArgs cl, const int32_t* __restrict__ rows, const int32_t* __restrict__ seg)
 {
     const int i = blockIdx.x;
+    // a kernel starts with cold caches, so every dependent load costs a trip to memory: the row number is requested
+    // together with the segment table (the sort writes rows[] for every position, 0 where there is no token)
+    const int row = rows[i];
     if (i >= seg[kSegValid]) return;
     const int c = cluster_at(seg, cl.count, i);
     if (c < 0) return;
     const int dim = cl.dim[c];
-    const char* src = (const char*)cl.E[c] + (int64_t)rows[i] * cl.lde[c] * ES;
+    const char* src = (const char*)cl.E[c] + (int64_t)row * cl.lde[c] * ES;
     char* dst = (char*)cl.g[c] + (int64_t)(i - seg[2 * c]) * cl.ldg[c] * ES;
     const float* z = cl.z[c];
     int k0 = 0;
@@ -516,36 +519,40 @@ template <int ES>
 __global__ __launch_bounds__(kScatterThreads) void embed_scatter_window_kernel(
     EmbedClusterArgs cl, const int32_t* __restrict__ rows, const int32_t* __restrict__ seg,
     const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_id,
-    float* __restrict__ head, float* __restrict__ tail, int64_t ldp)
+    float* __restrict__ head, float* __restrict__ tail, int64_t ldp, int n)
 {
     __shared__ const char* row_src[kScatterWindow];
     __shared__ char* row_dst[kScatterWindow];
     __shared__ int row_dim[kScatterWindow];    // 0: row not used
     __shared__ int row_flush[kScatterWindow];  // 0: keep adding, 1: round and store to dE, 2: store float32 partial
+    const int w0 = blockIdx.x * kScatterWindow;   // < n: the grid has ceil(n / window) windows
+    // A kernel starts with cold caches, so every dependent load costs a trip to memory.  What depends on the position
+    // alone is requested before the batch's extents are known: the run and the table row of this thread's position
+    // (rows[] is written for all n positions; run_id[] beyond the valid ones holds anything and is not used).
+    int u = 0, row = 0;
+    if (threadIdx.x < kScatterWindow) {
+        const int ic = min(w0 + (int)threadIdx.x, n - 1);
+        u = run_id[ic];
+        row = rows[ic];
+    }
     const int valid = seg[kSegValid];
-    const int w0 = blockIdx.x * kScatterWindow;
     if (w0 >= valid) return;
     const int w1 = (w0 + kScatterWindow < valid) ? w0 + kScatterWindow : valid;
+    // Rows of the window first (they depend on the segment table only), so that their loads below and the run
+    // extents travel together.
+    int c = -1, r0 = 0, r1 = 0;
     if (threadIdx.x < kScatterWindow) {
         const int t = threadIdx.x, i = w0 + t;
         row_dim[t] = 0; row_flush[t] = 0; row_src[t] = nullptr; row_dst[t] = nullptr;
         if (i < w1) {
-            const int u = run_id[i];
-            const int r0 = run_start[u], r1 = run_start[u + 1];
-            const int c = cluster_at(seg, cl.count, r0);
+            c = cluster_at(seg, cl.count, i);   // a run lies inside one cluster
             if (c >= 0 && cl.dE[c]) {
                 row_dim[t] = cl.dim[c];
                 row_src[t] = (const char*)cl.g[c] + (int64_t)(i - seg[2 * c]) * cl.ldg[c] * ES;
-                const int end = (r1 < w1) ? r1 : w1;
-                if (i == end - 1) {
-                    if (r0 >= w0 && r1 <= w1) {
-                        row_flush[t] = 1;
-                        row_dst[t] = (char*)cl.dE[c] + (int64_t)rows[r0] * cl.ldde[c] * ES;
-                    } else {
-                        row_flush[t] = 2;
-                        row_dst[t] = (char*)(((r0 < w0) ? head : tail) + (int64_t)blockIdx.x * ldp);
-                    }
-                }
+                r0 = run_start[u];
+                r1 = run_start[u + 1];
+            } else {
+                c = -1;
             }
         }
     }
@@ -554,6 +561,20 @@ __global__ __launch_bounds__(kScatterThreads) void embed_scatter_window_kernel(
     float v[kScatterWindow];
 #pragma unroll
     for (int t = 0; t < kScatterWindow; ++t) v[t] = (k < row_dim[t]) ? load_elem<ES>(row_src[t], k) : 0.0f;
+    if (threadIdx.x < kScatterWindow && c >= 0) {
+        const int t = threadIdx.x, i = w0 + t;
+        const int end = (r1 < w1) ? r1 : w1;
+        if (i == end - 1) {
+            if (r0 >= w0 && r1 <= w1) {
+                row_flush[t] = 1;
+                row_dst[t] = (char*)cl.dE[c] + (int64_t)row * cl.ldde[c] * ES;   // every position of a run has its row
+            } else {
+                row_flush[t] = 2;
+                row_dst[t] = (char*)(((r0 < w0) ? head : tail) + (int64_t)blockIdx.x * ldp);
+            }
+        }
+    }
+    __syncthreads();
     float acc = 0.0f;
 #pragma unroll
     for (int t = 0; t < kScatterWindow; ++t) {
@@ -573,21 +594,25 @@ template <int ES>
 __global__ __launch_bounds__(kScatterThreads) void embed_scatter_join_kernel(
     EmbedClusterArgs cl, const int32_t* __restrict__ rows, const int32_t* __restrict__ seg,
     const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_id, const float* __restrict__ head,
-    const float* __restrict__ tail, int64_t ldp)
+    const float* __restrict__ tail, int64_t ldp, int n)
 {
+    const int w0 = blockIdx.x * kScatterWindow;   // < n
+    // the window's last position, requested before the batch's extents are known (see the window kernel); only the
+    // batch's last window ends earlier and asks again
+    const int ic = min(w0 + kScatterWindow - 1, n - 1);
+    int u = run_id[ic], row = rows[ic];
     const int valid = seg[kSegValid];
-    const int w0 = blockIdx.x * kScatterWindow;
     if (w0 >= valid) return;
     const int w1 = (w0 + kScatterWindow < valid) ? w0 + kScatterWindow : valid;
+    if (w1 - 1 != ic) { u = run_id[w1 - 1]; row = rows[w1 - 1]; }
     // the run that leaves this window through its end, if it also starts here
-    const int u = run_id[w1 - 1];
     const int r0 = run_start[u], r1 = run_start[u + 1];
     if (r0 < w0 || r1 <= w1) return;
     const int c = cluster_at(seg, cl.count, r0);
     if (c < 0 || !cl.dE[c]) return;
     const int last = (r1 - 1) / kScatterWindow;
     const int dim = cl.dim[c];
-    char* dst = (char*)cl.dE[c] + (int64_t)rows[r0] * cl.ldde[c] * ES;
+    char* dst = (char*)cl.dE[c] + (int64_t)row * cl.ldde[c] * ES;
     for (int k = threadIdx.x; k < dim; k += kScatterThreads) {
         float acc = tail[(int64_t)blockIdx.x * ldp + k];
 #pragma unroll 8

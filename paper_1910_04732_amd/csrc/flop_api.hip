@@ -1889,13 +1889,13 @@ int flop_embed_bwd(flop_dtype dt, int64_t n_tokens, int32_t n_clusters, const fl
             float* head = (float*)(ws + L.scatter_head);
             float* tail = (float*)(ws + L.scatter_tail);
             if (dt == FLOP_BF16) {
-                hipLaunchKernelGGL(embed_scatter_window_kernel<2>, wgrid, block, 0, st, ca, rows, seg, run_start, run_id, head, tail, L.ld_scatter);
+                hipLaunchKernelGGL(embed_scatter_window_kernel<2>, wgrid, block, 0, st, ca, rows, seg, run_start, run_id, head, tail, L.ld_scatter, (int)n_tokens);
                 hipLaunchKernelGGL(embed_scatter_join_kernel<2>, grid, block, 0, st, ca, rows, seg, run_start, run_id,
-                                   (const float*)head, (const float*)tail, L.ld_scatter);
+                                   (const float*)head, (const float*)tail, L.ld_scatter, (int)n_tokens);
             } else {
-                hipLaunchKernelGGL(embed_scatter_window_kernel<4>, wgrid, block, 0, st, ca, rows, seg, run_start, run_id, head, tail, L.ld_scatter);
+                hipLaunchKernelGGL(embed_scatter_window_kernel<4>, wgrid, block, 0, st, ca, rows, seg, run_start, run_id, head, tail, L.ld_scatter, (int)n_tokens);
                 hipLaunchKernelGGL(embed_scatter_join_kernel<4>, grid, block, 0, st, ca, rows, seg, run_start, run_id,
-                                   (const float*)head, (const float*)tail, L.ld_scatter);
+                                   (const float*)head, (const float*)tail, L.ld_scatter, (int)n_tokens);
             }
             if (hipGetLastError() != hipSuccess) return FLOP_ERR_HIP;
         }
