@@ -602,6 +602,97 @@ def phases(flop, step, torch, cold=False) -> int:
     return 0
 
 
+def power() -> int:
+    """Board power while the path's workloads run: the driver's hwmon reading (power1_input, microwatts; power1_cap
+    is the limit) sampled every 20 ms over the second half of 3 s of back-to-back passes of (a) the wide layer
+    8192 x 3056 -> 9168 at rank 3056, fwd + bwd, rows padded to 128 bytes, (b) both layers of the C2 FFN pair,
+    fwd + bwd, (c) the matrix-core rate probe (MFMAs on register operands, no data movement), (d) a 1 GiB device
+    copy.  One JSON line per case."""
+    import glob
+    import threading
+
+    import torch
+
+    from paper_1910_04732_amd import flop
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    mons = [h for h in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")) if os.path.exists(os.path.join(h, "power1_input"))]
+    if not mons:
+        print("bench.py: no hwmon power reading on this box", file=sys.stderr)
+        return 3
+    src = os.path.join(mons[0], "power1_input")
+
+    def read(path):
+        try:
+            with open(path) as f:
+                return int(f.read().strip()) / 1e6
+        except (OSError, ValueError):
+            return None
+
+    def sample(case, fn, seconds=3.0, flops=None):
+        rows, stop = [], []
+
+        def loop():
+            while not stop:
+                rows.append((time.perf_counter(), read(src)))
+                time.sleep(0.02)
+        th = threading.Thread(target=loop, daemon=True)
+        th.start()
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            fn()
+            n += 1
+            if n % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        stop.append(1)
+        th.join()
+        w = [v for t, v in rows if v is not None and t - t0 > 0.5 * seconds]
+        rec = {"case": case, "watts_mean": round(sum(w) / len(w), 1), "watts_min": round(min(w), 1), "watts_max": round(max(w), 1),
+               "samples": len(w), "ms_per_pass": round(dt * 1e3 / n, 4), "watts_cap": read(os.path.join(mons[0], "power1_cap"))}
+        if flops:
+            rec["TFLOP_per_s"] = round(flops * n / dt / 1e12, 1)
+        print(json.dumps(rec), flush=True)
+
+    def layer(n, d, r, dout):
+        ld = lambda c: -(-c // 64) * 64
+        mk = lambda rows, cols, var: (torch.randn(rows, ld(cols), device=dev) * var ** 0.5).to(torch.bfloat16)[:, :cols]
+        out = lambda rows, cols: torch.empty(rows, ld(cols), dtype=torch.bfloat16, device=dev)[:, :cols]
+        t = dict(x=mk(n, d, 1.0), Q=mk(r, d, 1.0 / d), P=mk(dout, r, 1.0 / r), dy=mk(n, dout, 1.0), g=out(n, r), y=out(n, dout),
+                 dx=out(n, d), dQ=out(r, d), dP=out(dout, r), z=torch.rand(r, device=dev) + 0.1, dzda=torch.rand(r, device=dev),
+                 da=torch.empty(r, device=dev),
+                 ws=flop.workspace(flop.flop_workspace_bytes(flop.FLOP_OP_BWD, flop.FLOP_BF16, n, d, r, dout), dev))
+        t["flops"] = 6.0 * n * r * (d + dout)
+        return t
+
+    def step(t):
+        flop.flop_fwd(t["x"], t["Q"], t["P"], t["z"], t["g"], t["y"])
+        flop.flop_bwd(t["dy"], t["x"], t["Q"], t["P"], t["z"], t["dzda"], t["g"], t["dx"], t["dQ"], t["dP"], t["da"], t["ws"])
+
+    time.sleep(1.0)
+    idle = [read(src) for _ in range(20) if not time.sleep(0.02)]
+    print(json.dumps({"case": "idle", "watts_mean": round(sum(idle) / len(idle), 1), "source": src}), flush=True)
+    wide = layer(8192, 3056, 3056, 9168)
+    sample("wide layer 8192 x 3056 -> 9168, rank 3056, fwd + bwd", lambda: step(wide), flops=wide["flops"])
+    flop.flop_bench_force_tile_shape(0)   # measurement aid: 128x128 blocks instead of the library's 256x128
+    sample("the same with 128x128 blocks forced", lambda: step(wide), flops=wide["flops"])
+    flop.flop_bench_force_tile_shape(-1)
+    c2 = [layer(2048, 768, 768, 3072), layer(2048, 3072, 768, 768)]
+    sample("C2 FFN pair, fwd + bwd of both layers", lambda: [step(t) for t in c2], flops=sum(t["flops"] for t in c2))
+    sink = torch.empty(64, dtype=torch.float32, device=dev)
+    fl = flop.flop_mfma_probe(flop.FLOP_BF16, 8192, 2048, sink)
+    sample("matrix-core rate probe (MFMAs on register operands only)", lambda: flop.flop_mfma_probe(flop.FLOP_BF16, 8192, 2048, sink), flops=fl)
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    sample("1 GiB device copy", lambda: b.copy_(a))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -618,6 +709,7 @@ def main() -> int:
                     help="per-block phase times of the step's eight launches (entry, main loop, staging, stores) from the "
                          "measurement build of the library (libflop_hip_phases.so) instead of the step benchmark")
     ap.add_argument("--cold", action="store_true", help="with --phases: evict the operands from the last-level cache before every measured step")
+    ap.add_argument("--power", action="store_true", help="board power (hwmon) under the wide layer, the C2 layers, the matrix-core probe and a copy")
     ap.add_argument("--sweep", action="store_true", help="size sweep of the bandwidth-bound kernels instead of the step benchmark")
     ap.add_argument("--configs", action="store_true", help="time every workload configuration (C1..C5) instead of the step benchmark")
     ap.add_argument("--only", default="", help="with --configs: comma list of C1, C2, wide, C3, C4, softmax, C5; wide:plain, "
@@ -631,6 +723,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(the path would shard over tokens, each GPU running this same step on its rows)", file=sys.stderr)
         return 2
+    if args.power:
+        return power()
     if args.sweep:
         return sweep()
     if args.configs:
