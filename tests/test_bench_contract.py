@@ -43,3 +43,13 @@ def test_json_line():
     assert abs(r["frac_of_measured_peak"] - r["achieved"] / r["measured_mfma_peak"]) < 1e-3
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "TFLOP/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
+
+
+def test_measurement_modes_need_a_gpu():
+    """Without a GPU the measurement modes say so and exit with status 3 instead of falling back to anything."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    for mode in ("--power", "--phases"):
+        p = run_bench(mode)
+        assert p.returncode == 3 and p.stdout.strip() == "" and "bench.py:" in p.stderr, (mode, p.stderr[-500:])
