@@ -11,6 +11,9 @@
 //                                           (odd, 2 mod 4, 4 mod 8, 0 mod 8) with dense last rows, riders on
 //                                           and off, empty pending lists, boundary jobs with and without new gates
 //
+//   address_model padded                    rows padded to 16 bytes around extents that are not multiples of 8 elements
+//   address_model lowrank                   flop_fwd on layers whose second product takes the kernel for ranks up to 256
+//
 //   address_model case <bf16|f32> <extra> n d r dout [n d r dout ...]   the given layers, with and without new gates, every block shape
 //
 // Prints one line per case before running it, so that a report names its case.
@@ -258,12 +261,79 @@ int run_classes(int stride)
     return 0;
 }
 
+// The store-bound kernel for ranks up to 256 (y = g P^T with a short contraction): outputs large enough for the
+// library to choose it, rows padded to 16 bytes, ranks that end inside a 16-byte piece, ragged row and column
+// tails.  Every tensor ends where the interface allows it to: at the next multiple of 16 bytes after its last row's
+// last element (include/flop.h: every row, the last included, is addressable that far).
+int run_lowrank()
+{
+    static const int64_t cases[][4] = {   // n, d, r, dout
+        {4100, 72, 64, 2050}, {4099, 40, 41, 2051}, {8200, 40, 100, 8200}, {8195, 24, 200, 8201}, {8200, 24, 250, 8190},
+    };
+    const size_t es = 2;
+    for (const auto& c : cases) {
+        const int64_t n = c[0], d = c[1], r = c[2], dout = c[3];
+        auto ld = [](int64_t cols) { return (cols + 7) / 8 * 8; };
+        auto bytes = [&](int64_t rows, int64_t cols) { return (size_t)((rows - 1) * ld(cols) + (cols + 7) / 8 * 8) * es; };
+        printf("lowrank n=%ld d=%ld r=%ld dout=%ld\n", (long)n, (long)d, (long)r, (long)dout);
+        fflush(stdout);
+        Buf x(bytes(n, d)), Q(bytes(r, d)), P(bytes(dout, r)), g(bytes(n, r)), y(bytes(n, dout)), z = gates(r, 0.5f);
+        const unsigned long before = flop_model::g_launch.launches;
+        must(flop_fwd(FLOP_BF16, n, d, r, dout, x.p, ld(d), Q.p, ld(d), P.p, ld(r), z.f(), g.p, ld(r), y.p, ld(dout), nullptr, 0,
+                      nullptr), "flop_fwd");
+        if (flop_model::g_launch.launches != before + 2) { fprintf(stderr, "expected two launches\n"); return 1; }
+    }
+    return 0;
+}
+
+// Rows padded to 16 bytes around extents that are not multiples of 8 elements (the 410-wide matrices of a
+// Transformer layer in rows of 416, compacted ranks inside a wider buffer): the 16-byte transfer kernels read whole
+// chunks, so a row's last chunk reaches into its padding.  Tensors end at the next multiple of 16 bytes after the
+// last row's last element, as the interface allows.  Forward, backward and the deferred weight gradients, every
+// block shape.
+int run_padded()
+{
+    static const int64_t cases[][5] = {   // n, d, r, dout, extra elements of padding per row (multiple of 8)
+        {300, 203, 131, 77, 0}, {129, 410, 410, 1230, 0}, {257, 61, 306, 135, 8}, {70, 9, 3, 5, 0}, {333, 1029, 45, 67, 16},
+    };
+    const size_t es = 2;
+    for (const auto& c : cases)
+        for (int shape = -1; shape < flop_bench_tile_shapes(); ++shape) {
+            const int64_t n = c[0], d = c[1], r = c[2], dout = c[3], pad = c[4];
+            auto ld = [&](int64_t cols) { return (cols + 7) / 8 * 8 + pad; };
+            auto mk = [&](int64_t rows, int64_t cols) { return Buf((size_t)((rows - 1) * ld(cols) + (cols + 7) / 8 * 8) * es); };
+            must(flop_bench_force_tile_shape(shape), "flop_bench_force_tile_shape");
+            printf("padded n=%ld d=%ld r=%ld dout=%ld pad=%ld shape %s\n", (long)n, (long)d, (long)r, (long)dout, (long)pad,
+                   flop_bench_tile_shape_name(shape));
+            fflush(stdout);
+            Buf x = mk(n, d), Q = mk(r, d), P = mk(dout, r), dy = mk(n, dout), g = mk(n, r), y = mk(n, dout), dx = mk(n, d),
+                dQ = mk(r, d), dP = mk(dout, r), da((size_t)r * 4), z = gates(r, 0.5f), dz = gates(r, 0.1f);
+            Buf ws(flop_workspace_bytes(FLOP_OP_BWD, FLOP_BF16, n, d, r, dout));
+            must(flop_fwd(FLOP_BF16, n, d, r, dout, x.p, ld(d), Q.p, ld(d), P.p, ld(r), z.f(), g.p, ld(r), y.p, ld(dout), nullptr, 0,
+                          nullptr), "flop_fwd");
+            must(flop_bwd(FLOP_BF16, n, d, r, dout, dy.p, ld(dout), x.p, ld(d), Q.p, ld(d), P.p, ld(r), z.f(), dz.f(), g.p, ld(r),
+                          dx.p, ld(d), dQ.p, ld(d), dP.p, ld(r), da.f(), 0, ws.p, ws.bytes, nullptr), "flop_bwd");
+            flop_gate_grad_pending gi;
+            flop_weight_grad_pending wi;
+            must(flop_bwd_defer_weights(FLOP_BF16, n, d, r, dout, dy.p, ld(dout), x.p, ld(d), Q.p, ld(d), P.p, ld(r), z.f(), dz.f(),
+                                        g.p, ld(r), dx.p, ld(d), dQ.p, ld(d), dP.p, ld(r), da.f(), 0, ws.p, ws.bytes, nullptr, &gi,
+                                        &wi), "flop_bwd_defer_weights");
+            must(flop_weight_grad_finish(&wi, 1, nullptr), "flop_weight_grad_finish");
+            const flop_gate_grad_pending items[1] = {gi};
+            must(flop_gate_grad_finish(items, 1, nullptr), "flop_gate_grad_finish");
+        }
+    must(flop_bench_force_tile_shape(-1), "flop_bench_force_tile_shape");
+    return 0;
+}
+
 }  // namespace
 
 int main(int argc, char** argv)
 {
     int rc = 2;
     if (argc >= 4 && !strcmp(argv[1], "random")) rc = run_random(strtoull(argv[2], nullptr, 10), atoi(argv[3]));
+    else if (argc >= 2 && !strcmp(argv[1], "lowrank")) rc = run_lowrank();
+    else if (argc >= 2 && !strcmp(argv[1], "padded")) rc = run_padded();
     else if (argc >= 2 && !strcmp(argv[1], "classes")) rc = run_classes(argc >= 3 ? std::max(1, atoi(argv[2])) : 1);
     else if (argc >= 8 && !strcmp(argv[1], "case") && (argc - 4) % 4 == 0) {   // case <bf16|f32> <extra gates> n d r dout ...
         std::vector<std::array<int64_t, 4>> shapes;
@@ -278,7 +348,7 @@ int main(int argc, char** argv)
             }
         rc = 0;
     }
-    else fprintf(stderr, "usage: address_model random <seed> <cases> | classes [stride] | case <bf16|f32> <extra gates> n d r dout ...\n");
+    else fprintf(stderr, "usage: address_model random <seed> <cases> | classes [stride] | lowrank | padded | case <bf16|f32> <extra gates> n d r dout ...\n");
     if (rc == 0)
         printf("address model ok: %lu launches, %lu blocks, %lu transfers (%lu zero-filled)\n", flop_model::g_launch.launches,
                flop_model::g_launch.blocks, flop_model::g_launch.transfers, flop_model::g_launch.transfers_zero_filled);

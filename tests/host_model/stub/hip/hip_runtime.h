@@ -11,7 +11,7 @@
 // product sources.  What it drops: values.  Threads do not run in lockstep, so barriers are no-ops, wave
 // shuffles return the caller's own value, matrix instructions return their accumulator, LDS holds
 // whatever the last writer left, and static __shared__ arrays are per-thread locals.  Only kernels whose
-// addresses do not depend on such values are meaningful here (the contraction kernels, the gate, Eq.(3) and
+// addresses do not depend on such values are meaningful here (the contraction kernels, the store-bound kernel for small ranks, the gate, Eq.(3) and
 // gate-gradient kernels and the step-boundary blocks); the driver launches nothing else.
 #pragma once
 

@@ -5,7 +5,8 @@ blocks and threads and device pointers are heap pointers of exactly the tensors'
 address the host and device code compute - per tile, per lane, per transfer - is checked against the extent of
 its tensor.  It covers the contraction kernels with their epilogues, riders and fused column sums, the gate,
 Eq.(3) and gate-gradient kernels, on layers of every alignment class with gate vectors sliced at arbitrary
-offsets.  No GPU is involved.
+offsets, rows padded to 16 bytes around ragged extents, and the store-bound kernel for ranks up to 256.  No GPU is
+involved.
 """
 import os
 import shutil
@@ -45,3 +46,15 @@ def test_alignment_classes(model_binary):
 def test_random_layers(model_binary):
     # 1-4 layers of random shape per case, gate vectors at arbitrary offsets inside one array, 0-5000 extra gates
     _run(model_binary, "random", "7", "20")
+
+
+def test_padded_rows(model_binary):
+    # rows padded to 16 bytes around extents that are not multiples of 8 elements: the last 16-byte chunk of every row
+    # reaches into its padding; tensors end at the next multiple of 16 bytes after the last row's last element
+    _run(model_binary, "padded")
+
+
+def test_store_bound_kernel_for_small_ranks(model_binary):
+    # outputs of 8 M and 67 M elements, so that the library takes the kernel for ranks up to 256: ranks 64, 41, 100,
+    # 200 and 250 (every k-chunk variant, ranks that end inside a 16-byte piece), ragged row and column tails
+    _run(model_binary, "lowrank")
