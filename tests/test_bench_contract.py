@@ -53,3 +53,18 @@ def test_measurement_modes_need_a_gpu():
     for mode in ("--power", "--phases"):
         p = run_bench(mode)
         assert p.returncode == 3 and p.stdout.strip() == "" and "bench.py:" in p.stderr, (mode, p.stderr[-500:])
+
+
+@pytest.mark.gpu
+def test_power_report():
+    """bench.py --power: one JSON line per case; the readings lie between idle and the board's limit."""
+    p = run_bench("--power")
+    if p.returncode == 3 and "hwmon" in p.stderr:
+        pytest.skip("no board power reading on this box")
+    assert p.returncode == 0, p.stderr[-2000:]
+    rows = [json.loads(l) for l in p.stdout.splitlines() if l.startswith("{")]
+    assert rows[0]["case"] == "idle" and len(rows) == 6
+    for r in rows[1:]:
+        assert rows[0]["watts_mean"] * 0.9 <= r["watts_min"] <= r["watts_mean"] <= r["watts_max"]
+        assert r["watts_cap"] is None or r["watts_max"] <= 1.1 * r["watts_cap"]
+        assert r["samples"] >= 20 and r["ms_per_pass"] > 0
