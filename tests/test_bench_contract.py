@@ -33,6 +33,8 @@ def test_json_line():
     assert d["n_gpus"] == 1 and d["steps"] == 20 and d["warmup"] == 5
     assert d["unit"] == "TFLOP/s" and d["dtype"] == "bf16" and d["data"] == "synthetic" and d["vs_baseline"] is None
     assert d["higher_is_better"] is True and "workload" in d["config"] and "model" not in d["config"]
+    # the untimed steps that precede the warm-up (clock ramp) are stated in the line
+    assert d["config"]["clock_ramp"]["ms"] == 500.0 and d["config"]["clock_ramp"]["untimed_steps_before_warmup"] >= 50
     # value is the step's algorithmic flops over the measured step time
     assert abs(d["value"] - d["config"]["flops_per_step"] / (d["ms_per_step"] * 1e-3) / 1e12) <= 0.01 * d["value"]
     r = d["roofline"]
